@@ -1,0 +1,453 @@
+"""CPU oracle for the asymmetric-pool hybrid decode path (TEST INFRASTRUCTURE ONLY).
+
+This module is a plain, slow, float64 restatement of what the path computes:
+the 32-bit virtual handle and the virtual page table (Method, "Asymmetric
+Virtual Page Table" and Fig. 1), allocate/free with the capacity error and the
+capacity migration between the two pools (Method, "Dynamic Pool Rebalancing"),
+paged grouped-query decode attention over the KV-page pool and the Mamba-2
+style single-token state update in the SSM-block pool (Background, "KV Cache
+and SSM State Management": scatter-gather page lookups for KV, contiguous
+in-place read/write for SSM state).
+
+It exists so that tests, the smoke check and the benchmark's CPU-baseline leg
+can compare the GPU library with it.  Nothing in the product imports it, and
+it imports nothing from the product: it has its own handle codec, its own
+geometry arithmetic and its own page-layout index formulas.
+
+Parity pins: every function here is pinned by tests in tests/test_oracle_*.py
+(worked example of Fig. 1, closed-form unit sizes, dense attention through a
+library routine, unrolled recurrence closed form, two-counter capacity model,
+migration conservation laws).  Not pinned, because the paper's harness and
+traces are not available: the paper's OOM counts, goodput and bootstrap CIs
+("parity unpinned"; not attempted).
+
+Readings taken where the paper is silent are listed in the design notes and
+repeated next to the code that depends on them.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+# ----------------------------------------------------------------------------
+# Handle codec (Method, "Asymmetric Virtual Page Table"; Fig. 1: a 32-bit
+# handle = pool_id tag + page_id).  The paper does not give the bit split;
+# reading: 2-bit tag in the top bits (room for the third pool named under
+# Future Work), 30-bit page id.  All-ones is the invalid handle.
+# ----------------------------------------------------------------------------
+POOL_KV = 0
+POOL_SSM = 1
+N_POOLS = 2
+PAGE_ID_BITS = 30
+PAGE_ID_MASK = (1 << PAGE_ID_BITS) - 1
+INVALID_HANDLE = 0xFFFFFFFF
+UNMAPPED = 0xFFFFFFFF
+
+OK = 0
+ERR_CAPACITY = 1          # the paper's CapacityError
+ERR_INVALID_HANDLE = 2
+ERR_INVALID_ARG = 3
+
+
+def encode_handle(pool_id: int, page_id: int) -> int:
+    if not (0 <= pool_id < 4) or not (0 <= page_id <= PAGE_ID_MASK):
+        raise ValueError("handle field out of range")
+    return (pool_id << PAGE_ID_BITS) | page_id
+
+
+def decode_handle(h: int) -> Tuple[int, int]:
+    h = int(h) & 0xFFFFFFFF
+    return h >> PAGE_ID_BITS, h & PAGE_ID_MASK
+
+
+def round_up(v: int, m: int) -> int:
+    return (v + m - 1) // m * m
+
+
+# ----------------------------------------------------------------------------
+# Shapes and unit sizes (Method, "Asymmetric Virtual Page Table": a KV page is
+# attention_page_tokens x per_token_bytes, an SSM block is state_dim x
+# bytes_per_element; 128-byte slab alignment, 16-byte page alignment).
+# Reading: one KV page holds K and V of ONE attention layer for all KV heads,
+# mirroring the per-layer SSM block of Fig. 1's caption.
+# ----------------------------------------------------------------------------
+ELEM_BYTES = {"f32": 4, "bf16": 2}
+SLAB_ALIGN = 128
+PAGE_ALIGN = 16
+
+
+@dataclass(frozen=True)
+class Shape:
+    dtype: str            # element type of K, V, q, x, B, C: "f32" or "bf16"
+    page_tokens: int      # attention_page_tokens (paper default 16)
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ssm_heads: int        # H
+    ssm_headdim: int      # P
+    ssm_dstate: int       # N
+
+    @property
+    def elem_bytes(self) -> int:
+        return ELEM_BYTES[self.dtype]
+
+    @property
+    def per_token_bytes(self) -> int:
+        return 2 * self.n_kv_heads * self.head_dim * self.elem_bytes
+
+    @property
+    def state_dim(self) -> int:
+        return self.ssm_heads * self.ssm_headdim * self.ssm_dstate
+
+    def unit_bytes(self, pool: int) -> int:
+        if pool == POOL_KV:
+            raw = self.page_tokens * self.per_token_bytes
+        else:
+            raw = self.state_dim * 4          # state is carried in fp32
+        return round_up(raw, PAGE_ALIGN)
+
+
+def decode_elements(raw: np.ndarray, dtype: str) -> np.ndarray:
+    """Bytes -> float64 values.  bf16 is the top half of an IEEE fp32."""
+    if dtype == "f32":
+        return raw.view(np.float32).astype(np.float64)
+    u = raw.view(np.uint16).astype(np.uint32) << 16
+    return u.view(np.float32).astype(np.float64)
+
+
+def as_f64(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Input array (float32, or uint16 bit patterns for bf16) -> float64."""
+    a = np.ascontiguousarray(a)
+    if dtype == "bf16":
+        if a.dtype != np.uint16:
+            raise TypeError("bf16 inputs are passed as uint16 bit patterns")
+        return decode_elements(a.reshape(-1).view(np.uint8), "bf16").reshape(a.shape)
+    return a.astype(np.float64)
+
+
+@dataclass
+class MigrateResult:
+    code: int
+    units_copied: int = 0
+    recipient_gain: int = 0
+    bytes_wasted: int = 0
+    moves: List[Tuple[int, int, int]] = field(default_factory=list)  # (src, dst, vid)
+
+
+class Pools:
+    """Two pools in one arena behind one virtual page table.
+
+    Geometry (reading of "shrinking it at the high end of its address space
+    ... and the recipient pool grows", Method, "Dynamic Pool Rebalancing"):
+    KV slot s lives at byte s*unit_kv counted up from the arena base; SSM slot
+    i lives at usable - (i+1)*unit_ssm counted down from the arena top.  The
+    high ends of both pools face one shared gap in the middle.
+    """
+
+    def __init__(self, shape: Shape, arena_bytes: int, kv_capacity: int,
+                 ssm_capacity: int,
+                 slot_rank: Optional[Sequence[Optional[np.ndarray]]] = None,
+                 max_vid: Optional[Sequence[int]] = None,
+                 with_data: bool = True):
+        self.shape = shape
+        self.unit = [shape.unit_bytes(POOL_KV), shape.unit_bytes(POOL_SSM)]
+        self.usable = arena_bytes // SLAB_ALIGN * SLAB_ALIGN
+        self.max_slots = [self.usable // u for u in self.unit]
+        need = kv_capacity * self.unit[0] + ssm_capacity * self.unit[1]
+        if need > self.usable:
+            raise ValueError("initial capacities do not fit the arena")
+        self.capacity = [int(kv_capacity), int(ssm_capacity)]
+        self.gap = self.usable - need
+        self.max_vid = list(max_vid) if max_vid is not None else list(self.max_slots)
+        self.rank = []
+        for p in range(N_POOLS):
+            r = None if slot_rank is None else slot_rank[p]
+            if r is None:
+                r = np.arange(self.max_slots[p], dtype=np.int64)
+            r = np.asarray(r, dtype=np.int64)
+            if r.shape != (self.max_slots[p],) or \
+                    not np.array_equal(np.sort(r), np.arange(self.max_slots[p])):
+                raise ValueError("slot_rank must be a permutation of all possible slots")
+            self.rank.append(r)
+        # the virtual page table and its reverse map
+        self.slot_of = [np.full(self.max_vid[p], UNMAPPED, dtype=np.int64) for p in range(N_POOLS)]
+        self.vid_of = [np.full(self.max_slots[p], UNMAPPED, dtype=np.int64) for p in range(N_POOLS)]
+        self.arena = np.zeros(self.usable, dtype=np.uint8) if with_data else None
+        # counters (the 64-bit logical operation counter of the paper + outcome counters)
+        self.ops = 0
+        self.capacity_errors = 0
+        self.migrations = 0
+        self.units_copied = 0
+        self.bytes_migrated = 0
+        self.bytes_wasted = 0
+
+    # ---- geometry -----------------------------------------------------------
+    def byte_offset(self, pool: int, slot: int) -> int:
+        if pool == POOL_KV:
+            return slot * self.unit[POOL_KV]
+        return self.usable - (slot + 1) * self.unit[POOL_SSM]
+
+    # ---- table ---------------------------------------------------------------
+    def resolve(self, h: int) -> Optional[Tuple[int, int, int]]:
+        """handle -> (pool, slot, byte offset), or None if not a live handle."""
+        pool, vid = decode_handle(h)
+        if pool >= N_POOLS or vid >= self.max_vid[pool]:
+            return None
+        slot = int(self.slot_of[pool][vid])
+        if slot == UNMAPPED:
+            return None
+        return pool, slot, self.byte_offset(pool, slot)
+
+    def live_count(self, pool: int) -> int:
+        return int(np.count_nonzero(self.vid_of[pool][: self.capacity[pool]] != UNMAPPED))
+
+    def free_count(self, pool: int) -> int:
+        return self.capacity[pool] - self.live_count(pool)
+
+    def _best_free_slot(self, pool: int, below: int) -> int:
+        """Free slot of lowest rank among slots < below (reading: placement is a
+        caller-given rank order, so that physical placement can be permuted)."""
+        free = np.flatnonzero(self.vid_of[pool][:below] == UNMAPPED)
+        return int(free[np.argmin(self.rank[pool][free])])
+
+    def _lowest_free_vid(self, pool: int) -> Optional[int]:
+        free = np.flatnonzero(self.slot_of[pool] == UNMAPPED)
+        return int(free[0]) if free.size else None
+
+    # ---- allocate / free (Method, "Dynamic Pool Rebalancing": allocate()
+    #      raises CapacityError when the tagged pool cannot serve the request) --
+    def alloc(self, pool: int, n: int) -> Tuple[int, List[int]]:
+        if pool not in (POOL_KV, POOL_SSM) or n <= 0:
+            return ERR_INVALID_ARG, []
+        self.ops += 1
+        free_vids = int(np.count_nonzero(self.slot_of[pool] == UNMAPPED))
+        if self.free_count(pool) < n or free_vids < n:
+            self.capacity_errors += 1
+            return ERR_CAPACITY, []
+        out = []
+        for _ in range(n):
+            vid = self._lowest_free_vid(pool)
+            slot = self._best_free_slot(pool, self.capacity[pool])
+            self.slot_of[pool][vid] = slot
+            self.vid_of[pool][slot] = vid
+            if pool == POOL_SSM and self.arena is not None:
+                # a new sequence starts from the zero state
+                off = self.byte_offset(pool, slot)
+                self.arena[off: off + self.unit[pool]] = 0
+            out.append(encode_handle(pool, vid))
+        return OK, out
+
+    def free(self, handles: Sequence[int]) -> int:
+        if len(handles) == 0:
+            return ERR_INVALID_ARG
+        self.ops += 1
+        seen = set()
+        for h in handles:
+            if self.resolve(h) is None or int(h) in seen:
+                return ERR_INVALID_HANDLE
+            seen.add(int(h))
+        for h in handles:
+            pool, vid = decode_handle(h)
+            slot = int(self.slot_of[pool][vid])
+            self.slot_of[pool][vid] = UNMAPPED
+            self.vid_of[pool][slot] = UNMAPPED
+        return OK
+
+    # ---- capacity migration (Method, "Dynamic Pool Rebalancing") -------------
+    def migrate(self, donor: int, n: int) -> MigrateResult:
+        """Move the capacity of n donor units to the other pool.
+
+        The donor shrinks at the high end of its slot range; live units found
+        there are first copied to free slots below the new capacity (the
+        paper's prototype needs no copy because its tensors are oversized; a
+        single arena does).  Freed bytes plus the gap left by earlier
+        migrations become floor(bytes / recipient unit) new recipient slots;
+        the remainder is the paper's wasted bytes ("donor bytes freed modulo
+        the recipient page size") and stays in the gap.  All-or-nothing: a
+        request the donor cannot satisfy changes nothing (rollback clause).
+        """
+        if donor not in (POOL_KV, POOL_SSM) or n <= 0:
+            return MigrateResult(ERR_INVALID_ARG)
+        self.ops += 1
+        if n > self.capacity[donor] or self.free_count(donor) < n:
+            return MigrateResult(ERR_CAPACITY)
+        recip = 1 - donor
+        newcap = self.capacity[donor] - n
+        res = MigrateResult(OK)
+        for s in range(newcap, self.capacity[donor]):
+            vid = int(self.vid_of[donor][s])
+            if vid == UNMAPPED:
+                continue
+            dst = self._best_free_slot(donor, newcap)
+            if self.arena is not None:
+                so, do = self.byte_offset(donor, s), self.byte_offset(donor, dst)
+                u = self.unit[donor]
+                self.arena[do: do + u] = self.arena[so: so + u]
+            self.vid_of[donor][dst] = vid
+            self.vid_of[donor][s] = UNMAPPED
+            self.slot_of[donor][vid] = dst
+            res.moves.append((s, dst, vid))
+        self.capacity[donor] = newcap
+        avail = self.gap + n * self.unit[donor]
+        gain = avail // self.unit[recip]
+        self.gap = avail % self.unit[recip]
+        self.capacity[recip] += gain
+        res.units_copied = len(res.moves)
+        res.recipient_gain = gain
+        res.bytes_wasted = self.gap
+        self.migrations += 1
+        self.units_copied += res.units_copied
+        self.bytes_migrated += n * self.unit[donor]
+        self.bytes_wasted += res.bytes_wasted
+        return res
+
+    def stats(self) -> dict:
+        return {
+            "capacity": tuple(self.capacity),
+            "live": (self.live_count(0), self.live_count(1)),
+            "free": (self.free_count(0), self.free_count(1)),
+            "gap_bytes": self.gap,
+            "ops": self.ops,
+            "capacity_errors": self.capacity_errors,
+            "migrations": self.migrations,
+            "units_copied": self.units_copied,
+            "bytes_migrated": self.bytes_migrated,
+            "bytes_wasted": self.bytes_wasted,
+        }
+
+    # ---- raw unit access by handle ------------------------------------------
+    def unit_view(self, h: int) -> np.ndarray:
+        r = self.resolve(h)
+        if r is None:
+            raise KeyError("not a live handle: 0x%08x" % int(h))
+        pool, _, off = r
+        return self.arena[off: off + self.unit[pool]]
+
+    # ---- in-page layout -------------------------------------------------------
+    # The paper does not fix the layout inside a KV page.  Layout used here
+    # (x = 16 bytes / element size, T = page_tokens):
+    #   K element (kv head g, token t, dim d) at element index
+    #       ((g*(D/x) + d//x)*T + t)*x + d%x
+    #   V element (g, t, d) at element index  Hkv*T*D + (g*D + d)*T + t
+    def _page_to_kv(self, raw: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+        sh = self.shape
+        T, G, D = sh.page_tokens, sh.n_kv_heads, sh.head_dim
+        x = 16 // sh.elem_bytes
+        e = decode_elements(raw[: 2 * T * G * D * sh.elem_bytes], sh.dtype)
+        k = e[: G * T * D].reshape(G, D // x, T, x).transpose(2, 0, 1, 3).reshape(T, G, D)
+        v = e[G * T * D:].reshape(G, D, T).transpose(2, 0, 1)
+        return k, v          # both [T][G][D]
+
+    def kv_element_offset(self, which: str, g: int, t: int, d: int) -> int:
+        """Byte offset inside a page of one K or V element (layout above)."""
+        sh = self.shape
+        T, G, D = sh.page_tokens, sh.n_kv_heads, sh.head_dim
+        x = 16 // sh.elem_bytes
+        if which == "k":
+            idx = ((g * (D // x) + d // x) * T + t) * x + d % x
+        else:
+            idx = G * T * D + (g * D + d) * T + t
+        return idx * sh.elem_bytes
+
+    def write_kv_token(self, h: int, t: int, k_row: np.ndarray, v_row: np.ndarray) -> None:
+        """Store one token's K and V ([Hkv][D], raw element bit patterns:
+        float32 or uint16) into token slot t of the page behind handle h."""
+        sh = self.shape
+        page = self.unit_view(h)
+        kb = np.ascontiguousarray(k_row).view(np.uint8).reshape(sh.n_kv_heads, sh.head_dim, sh.elem_bytes)
+        vb = np.ascontiguousarray(v_row).view(np.uint8).reshape(sh.n_kv_heads, sh.head_dim, sh.elem_bytes)
+        for g in range(sh.n_kv_heads):
+            for d in range(sh.head_dim):
+                o = self.kv_element_offset("k", g, t, d)
+                page[o: o + sh.elem_bytes] = kb[g, d]
+                o = self.kv_element_offset("v", g, t, d)
+                page[o: o + sh.elem_bytes] = vb[g, d]
+
+    # ---- paged grouped-query decode attention ---------------------------------
+    def paged_attention(self, handles: np.ndarray, ctx: np.ndarray, q: np.ndarray) -> np.ndarray:
+        """o[r, j] = softmax_t(q[r, j] . K_t[g] / sqrt(D)) . V[:, g],  g = j // (Hq/Hkv),
+        over the ctx[r] tokens held in pages handles[r, 0 .. ceil(ctx/T)-1].
+        Token slots at or beyond ctx[r] in the last page are never read into
+        the result.  q: [batch][Hq][D] in the element dtype.  Returns float64."""
+        sh = self.shape
+        T, Hq, G, D = sh.page_tokens, sh.n_q_heads, sh.n_kv_heads, sh.head_dim
+        qf = as_f64(q, sh.dtype)
+        batch = len(ctx)
+        o = np.zeros((batch, Hq, D), dtype=np.float64)
+        for r in range(batch):
+            n_tok = int(ctx[r])
+            if n_tok == 0:
+                continue                      # no tokens: output row defined as zero
+            n_pages = -(-n_tok // T)
+            K = np.empty((n_pages * T, G, D))
+            V = np.empty((n_pages * T, G, D))
+            for i in range(n_pages):
+                res = self.resolve(int(handles[r, i]))
+                if res is None or res[0] != POOL_KV:
+                    raise KeyError("request %d page %d: not a live KV handle" % (r, i))
+                k, v = self._page_to_kv(self.arena[res[2]: res[2] + self.unit[POOL_KV]])
+                K[i * T: (i + 1) * T] = k
+                V[i * T: (i + 1) * T] = v
+            K, V = K[:n_tok], V[:n_tok]
+            for j in range(Hq):
+                g = j // (Hq // G)
+                s = (K[:, g, :] * qf[r, j][None, :]).sum(axis=1) / math.sqrt(D)
+                p = np.exp(s - s.max())
+                p /= p.sum()
+                o[r, j] = (p[:, None] * V[:, g, :]).sum(axis=0)
+        return o
+
+    # ---- single-token SSM state update ----------------------------------------
+    def ssm_step(self, handles: np.ndarray, x: np.ndarray, dt: np.ndarray, A: np.ndarray,
+                 B: np.ndarray, C: np.ndarray) -> np.ndarray:
+        """For request r, head h, channel p, state index n (state block [H][P][N], fp32):
+             a = exp(dt[r,h] * A[h])
+             S[h,p,n] <- a * S[h,p,n] + dt[r,h] * x[r,h,p] * B[r,n]
+             y[r,h,p] = sum_n S[h,p,n] * C[r,n]          (with the updated S)
+        The block is updated in place (stored rounded once to fp32); y uses the
+        updated value before that rounding.  x: [batch][H][P], B, C: [batch][N]
+        in the element dtype; dt: [batch][H] fp32; A: [H] fp32.  Returns float64."""
+        sh = self.shape
+        H, P, N = sh.ssm_heads, sh.ssm_headdim, sh.ssm_dstate
+        xf, Bf, Cf = as_f64(x, sh.dtype), as_f64(B, sh.dtype), as_f64(C, sh.dtype)
+        dtf, Af = np.asarray(dt, dtype=np.float64), np.asarray(A, dtype=np.float64)
+        batch = len(handles)
+        y = np.zeros((batch, H, P), dtype=np.float64)
+        for r in range(batch):
+            res = self.resolve(int(handles[r]))
+            if res is None or res[0] != POOL_SSM:
+                raise KeyError("request %d: not a live SSM handle" % r)
+            blk = self.arena[res[2]: res[2] + H * P * N * 4].view(np.float32).reshape(H, P, N)
+            S = blk.astype(np.float64)
+            a = np.exp(dtf[r] * Af)                                   # [H]
+            S = a[:, None, None] * S + (dtf[r][:, None] * xf[r])[:, :, None] * Bf[r][None, None, :]
+            y[r] = (S * Cf[r][None, None, :]).sum(axis=2)
+            blk[...] = S.astype(np.float32)
+        return y
+
+    # ---- one hybrid decode step ------------------------------------------------
+    def decode_step(self, layer_kinds: Sequence[int], kv_handles: np.ndarray, ctx: np.ndarray,
+                    q: np.ndarray, ssm_handles: np.ndarray, x: np.ndarray, dt: np.ndarray,
+                    A: np.ndarray, B: np.ndarray, C: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+        """Layers in model order (0 = attention, 1 = SSM).  Per-kind arrays are
+        indexed by the layer's ordinal among layers of its kind:
+        kv_handles [n_attn][batch][max_pages], q [n_attn][batch][Hq][D],
+        ssm_handles [n_ssm][batch], x [n_ssm][batch][H][P], dt [n_ssm][batch][H],
+        A [n_ssm][H], B, C [n_ssm][batch][N].  The step does not append a token:
+        ctx counts tokens already resident.  Returns (o [n_attn]..., y [n_ssm]...)."""
+        o, y = [], []
+        ia = iss = 0
+        for kind in layer_kinds:
+            if kind == 0:
+                o.append(self.paged_attention(kv_handles[ia], ctx, q[ia]))
+                ia += 1
+            else:
+                y.append(self.ssm_step(ssm_handles[iss], x[iss], dt[iss], A[iss], B[iss], C[iss]))
+                iss += 1
+        sh = self.shape
+        o = np.stack(o) if o else np.zeros((0, len(ctx), sh.n_q_heads, sh.head_dim))
+        y = np.stack(y) if y else np.zeros((0, len(ctx), sh.ssm_heads, sh.ssm_headdim))
+        return o, y
