@@ -1,0 +1,209 @@
+/*
+ * avmp.h - C ABI of the MI355X hybrid decode path over asymmetric pools.
+ *
+ * Two physically distinct pools, KV pages and SSM state blocks, live in ONE
+ * caller-owned device arena behind one 32-bit virtual handle space (paper:
+ * Method, "Asymmetric Virtual Page Table", Fig. 1).  The library keeps the
+ * virtual page table on the host, mirrors it on the device, and runs the steps
+ * that read through it as gfx950 kernels: handle translation, paged
+ * grouped-query decode attention, the single-token SSM state update done in
+ * place, and the capacity migration that copies units and rewrites the table
+ * (Method, "Dynamic Pool Rebalancing").
+ *
+ * Conventions
+ *  - plain C, int status returns, no callbacks; out-parameters are written
+ *    only on AVMP_OK; a failing call leaves every observable unchanged except
+ *    the logical operation counter where stated.
+ *  - "host" / "device" on a pointer says where the memory must live.  The
+ *    caller owns the arena, every input/output buffer and the stream; the
+ *    library owns its metadata, the device table mirror and a work buffer.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    avmp_decode_step, avmp_migrate, avmp_flush and avmp_translate are
+ *    asynchronous on it.  All device work of one pools object must be issued
+ *    on one stream or be ordered by the caller.
+ *  - not thread-safe: one thread per pools object (the paper's allocator is
+ *    single-process).
+ *
+ * Arena geometry.  usable = arena_bytes rounded down to 128.  KV slot s is at
+ * arena + s*unit_kv (ascending from the base); SSM slot i is at
+ * arena + usable - (i+1)*unit_ssm (descending from the top).  The high ends of
+ * both slot ranges face one shared gap, so "the donor shrinks at the high end
+ * of its address space and the recipient grows" holds in a single arena.
+ * Slab anchors are 128-byte aligned, units 16-byte aligned (Method,
+ * "Asymmetric Virtual Page Table").
+ *
+ * Layout inside a KV page (not fixed by the paper; chosen so that a wavefront's
+ * 16-byte loads are contiguous AND already in matrix-core operand order).
+ * With T = 16 tokens, G = KV heads, D = head_dim, x = 16 / element_bytes:
+ *    K element (g, t, d) at element index ((g*(D/x) + d/x)*T + t)*x + d%x
+ *    V element (g, t, d) at element index G*T*D + (g*D + d)*T + t
+ * An SSM block is fp32 [ssm_heads][ssm_headdim][ssm_dstate], row-major.
+ */
+#ifndef AVMP_H
+#define AVMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* 32-bit virtual handle: bits [31:30] pool tag, bits [29:0] virtual page id
+ * (Fig. 1: pool_id | page_id).  All-ones is never a valid handle. */
+typedef uint32_t avmp_handle_t;
+#define AVMP_PAGE_ID_BITS 30u
+#define AVMP_INVALID_HANDLE 0xFFFFFFFFu
+
+enum {
+  AVMP_OK = 0,
+  AVMP_ERR_CAPACITY = 1,        /* the paper's CapacityError */
+  AVMP_ERR_INVALID_HANDLE = 2,
+  AVMP_ERR_INVALID_ARG = 3,
+  AVMP_ERR_DEVICE = 4           /* a HIP call failed, or no device attached */
+};
+enum { AVMP_POOL_KV = 0, AVMP_POOL_SSM = 1 };
+enum { AVMP_F32 = 0, AVMP_BF16 = 1 };
+enum { AVMP_LAYER_ATTENTION = 0, AVMP_LAYER_SSM = 1 };
+
+typedef struct avmp_pools avmp_pools_t;     /* opaque, owned by the library */
+
+typedef struct avmp_config {
+  uint32_t dtype;                  /* AVMP_F32 / AVMP_BF16: element type of K, V, q, x, B, C */
+  uint32_t attention_page_tokens;  /* tokens per KV page; only 16 (the paper's default) */
+  uint32_t n_q_heads;              /* multiple of n_kv_heads */
+  uint32_t n_kv_heads;
+  uint32_t head_dim;               /* multiple of 16/element_bytes */
+  uint32_t ssm_heads;              /* H */
+  uint32_t ssm_headdim;            /* P */
+  uint32_t ssm_dstate;             /* N: power of two, 4..256 */
+  uint32_t kv_capacity;            /* initial KV pool capacity in pages */
+  uint32_t ssm_capacity;           /* initial SSM pool capacity in blocks */
+  uint32_t max_vid[2];             /* virtual ids per pool; 0 = as many as slots could ever exist */
+  const uint32_t* slot_rank[2];    /* host, or NULL = identity.  A permutation of
+                                      [0, max_slots[pool]): allocation takes the free slot of
+                                      LOWEST rank below the pool's capacity.  Copied at create. */
+} avmp_config_t;
+
+typedef struct avmp_geometry {
+  uint64_t unit_bytes[2];          /* KV page bytes, SSM block bytes (rounded up to 16) */
+  uint64_t usable_bytes;
+  uint32_t max_slots[2];           /* usable_bytes / unit_bytes[pool] */
+} avmp_geometry_t;
+
+typedef struct avmp_migrate_result {
+  uint32_t units_copied;           /* live donor units moved out of the vacated range */
+  uint32_t recipient_gain;         /* new recipient slots */
+  uint64_t bytes_wasted;           /* (gap before + n*unit_donor) mod unit_recipient: the paper's
+                                      wasted bytes; kept as the gap and reused next time */
+} avmp_migrate_result_t;
+
+typedef struct avmp_stats {
+  uint32_t capacity[2];
+  uint32_t live[2];
+  uint32_t free_units[2];
+  uint64_t gap_bytes;
+  uint64_t ops;                    /* logical operation counter: alloc/free/migrate calls that
+                                      passed argument validation, successful or not */
+  uint64_t capacity_errors;        /* avmp_alloc calls refused with AVMP_ERR_CAPACITY */
+  uint64_t migrations;
+  uint64_t units_copied;
+  uint64_t bytes_migrated;         /* sum of n*unit_donor over successful migrations */
+  uint64_t bytes_wasted;           /* sum of per-migration bytes_wasted */
+} avmp_stats_t;
+
+/* One hybrid decode step: layers in model order; per-kind arrays are indexed by
+ * the layer's ordinal among layers of its kind.  The step does not append a
+ * token: ctx counts tokens already resident.  Two requests of one batch must
+ * not name the same SSM handle. */
+typedef struct avmp_step {
+  uint32_t batch;
+  uint32_t n_layers;
+  const uint8_t* layer_kind;         /* host [n_layers]: AVMP_LAYER_* */
+  uint32_t max_pages;                /* row stride of kv_handles; >= ceil(max ctx / 16) */
+  const avmp_handle_t* kv_handles;   /* device [n_attn][batch][max_pages]; entries at or beyond
+                                        ceil(ctx/16) are ignored */
+  const uint32_t* ctx;               /* device [batch] tokens resident per request (may be 0) */
+  const void* q;                     /* device [n_attn][batch][n_q_heads][head_dim] elements */
+  float* o;                          /* device [n_attn][batch][n_q_heads][head_dim] fp32 out */
+  const avmp_handle_t* ssm_handles;  /* device [n_ssm][batch] */
+  const void* x;                     /* device [n_ssm][batch][H][P] elements */
+  const float* dt;                   /* device [n_ssm][batch][H] fp32, already positive */
+  const float* A;                    /* device [n_ssm][H] fp32 (negative decay rates) */
+  const void* B;                     /* device [n_ssm][batch][N] elements */
+  const void* C;                     /* device [n_ssm][batch][N] elements */
+  float* y;                          /* device [n_ssm][batch][H][P] fp32 out */
+} avmp_step_t;
+
+/* Size arithmetic of Method, "Asymmetric Virtual Page Table": KV page =
+ * attention_page_tokens x per_token_bytes (K and V of one attention layer, all
+ * KV heads), SSM block = state_dim x 4 bytes; both rounded up to 16.
+ * Host only.  AVMP_ERR_INVALID_ARG on unsupported shapes. */
+int avmp_geometry(const avmp_config_t* cfg, size_t arena_bytes, avmp_geometry_t* out);
+
+/* Create the two pools over a caller-owned arena (Method, "Asymmetric Virtual
+ * Page Table": KVPagesStore + SSMBlocksStore behind one VirtualPageTable).
+ * arena_dev: device pointer, 128-byte aligned, arena_bytes long, must outlive
+ * the pools.  arena_dev == NULL creates metadata-only pools (the paper's
+ * prototype mode: tables and counters, no data movement); on such pools
+ * avmp_migrate updates tables only and every device entry point returns
+ * AVMP_ERR_DEVICE.  Initial capacities must fit: else AVMP_ERR_INVALID_ARG. */
+int avmp_pools_create(const avmp_config_t* cfg, void* arena_dev, size_t arena_bytes,
+                      avmp_pools_t** out);
+int avmp_pools_destroy(avmp_pools_t* pools);
+
+/* allocate() of Method, "Dynamic Pool Rebalancing": take n units of `pool`.
+ * All-or-nothing.  Each unit gets the lowest free virtual id and the
+ * best-ranked free slot below the pool's capacity; out[0..n) (host) receives
+ * the handles.  AVMP_ERR_CAPACITY (counted) if fewer than n units are free.
+ * New SSM blocks read as zero: the zero fill is queued and executed on the
+ * stream of the next avmp_flush / avmp_decode_step / avmp_migrate, so a caller
+ * that writes a block itself must call avmp_flush first. n == 0: INVALID_ARG. */
+int avmp_alloc(avmp_pools_t* pools, int pool, uint32_t n, avmp_handle_t* out);
+
+/* Return n units (host array of handles, pools may be mixed).  Any stale,
+ * duplicate or malformed handle: AVMP_ERR_INVALID_HANDLE, nothing freed. */
+int avmp_free(avmp_pools_t* pools, const avmp_handle_t* handles, uint32_t n);
+
+/* Capacity migration of Method, "Dynamic Pool Rebalancing": the donor pool
+ * shrinks by n_donor_units at the high end of its slot range and the other
+ * pool grows.  Live donor units in the vacated range are first copied on the
+ * device to the best-ranked free slots below the new capacity and the table is
+ * rewritten (handles stay valid).  All-or-nothing (the paper's rollback
+ * clause): AVMP_ERR_CAPACITY if the donor has fewer than n free units. */
+int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, void* stream,
+                 avmp_migrate_result_t* out);
+
+/* One hybrid decode step (translation + paged GQA attention + SSM update) for
+ * every layer of `step`, enqueued on `stream`.  Attention per (request r, query
+ * head j, g = j / (n_q_heads/n_kv_heads)): o = softmax_t(q.K_t[g]/sqrt(D)) . V[g]
+ * over the ctx[r] resident tokens; SSM per (r, h, p, n): a = exp(dt*A),
+ * S <- a*S + dt*x*B[n] in place, y = sum_n S*C[n] with the updated S. */
+int avmp_decode_step(avmp_pools_t* pools, const avmp_step_t* step, void* stream);
+
+/* Push queued table updates and zero fills to the device on `stream`. */
+int avmp_flush(avmp_pools_t* pools, void* stream);
+
+/* Device-side translation of n handles (device array) to byte offsets from the
+ * arena base (device array, UINT64_MAX for handles that do not resolve). */
+int avmp_translate(avmp_pools_t* pools, const avmp_handle_t* handles_dev, uint32_t n,
+                   uint64_t* offsets_dev, void* stream);
+
+/* Host-side resolve (Fig. 1's lookup): handle -> pool, physical slot, byte
+ * offset from the arena base.  AVMP_ERR_INVALID_HANDLE if not live. */
+int avmp_resolve(const avmp_pools_t* pools, avmp_handle_t h, uint32_t* pool, uint32_t* slot,
+                 uint64_t* byte_off);
+
+int avmp_stats(const avmp_pools_t* pools, avmp_stats_t* out);
+
+/* Synchronise `stream`, then report and reset the number of handles that the
+ * kernels could not translate (such pages/blocks are skipped, never touched). */
+int avmp_device_faults(avmp_pools_t* pools, void* stream, uint64_t* out);
+
+/* Text of the last error raised on the calling thread ("" if none). */
+const char* avmp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AVMP_H */

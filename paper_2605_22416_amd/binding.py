@@ -1,0 +1,211 @@
+"""ctypes binding of libavmp.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/avmp.h).
+Device buffers are passed as torch tensors (their data_ptr is taken) or as
+integer addresses; streams as torch streams or integer hipStream_t values.
+There is no fallback: if the native library is missing, importing this module
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libavmp.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "native library %s is missing: build it with `python -m paper_2605_22416_amd.build` "
+        "(there is no CPU fallback)" % LIB_PATH)
+lib = C.CDLL(LIB_PATH)
+
+AVMP_OK, AVMP_ERR_CAPACITY, AVMP_ERR_INVALID_HANDLE, AVMP_ERR_INVALID_ARG, AVMP_ERR_DEVICE = range(5)
+AVMP_POOL_KV, AVMP_POOL_SSM = 0, 1
+AVMP_F32, AVMP_BF16 = 0, 1
+AVMP_LAYER_ATTENTION, AVMP_LAYER_SSM = 0, 1
+AVMP_INVALID_HANDLE = 0xFFFFFFFF
+
+
+class avmp_config_t(C.Structure):
+    _fields_ = [("dtype", C.c_uint32), ("attention_page_tokens", C.c_uint32),
+                ("n_q_heads", C.c_uint32), ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
+                ("ssm_heads", C.c_uint32), ("ssm_headdim", C.c_uint32), ("ssm_dstate", C.c_uint32),
+                ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
+                ("max_vid", C.c_uint32 * 2), ("slot_rank", C.POINTER(C.c_uint32) * 2)]
+
+
+class avmp_geometry_t(C.Structure):
+    _fields_ = [("unit_bytes", C.c_uint64 * 2), ("usable_bytes", C.c_uint64),
+                ("max_slots", C.c_uint32 * 2)]
+
+
+class avmp_migrate_result_t(C.Structure):
+    _fields_ = [("units_copied", C.c_uint32), ("recipient_gain", C.c_uint32),
+                ("bytes_wasted", C.c_uint64)]
+
+
+class avmp_stats_t(C.Structure):
+    _fields_ = [("capacity", C.c_uint32 * 2), ("live", C.c_uint32 * 2), ("free_units", C.c_uint32 * 2),
+                ("gap_bytes", C.c_uint64), ("ops", C.c_uint64), ("capacity_errors", C.c_uint64),
+                ("migrations", C.c_uint64), ("units_copied", C.c_uint64),
+                ("bytes_migrated", C.c_uint64), ("bytes_wasted", C.c_uint64)]
+
+
+class avmp_step_t(C.Structure):
+    _fields_ = [("batch", C.c_uint32), ("n_layers", C.c_uint32), ("layer_kind", C.c_void_p),
+                ("max_pages", C.c_uint32), ("kv_handles", C.c_void_p), ("ctx", C.c_void_p),
+                ("q", C.c_void_p), ("o", C.c_void_p), ("ssm_handles", C.c_void_p),
+                ("x", C.c_void_p), ("dt", C.c_void_p), ("A", C.c_void_p), ("B", C.c_void_p),
+                ("C", C.c_void_p), ("y", C.c_void_p)]
+
+
+_P = C.c_void_p
+lib.avmp_last_error.restype = C.c_char_p
+lib.avmp_last_error.argtypes = []
+lib.avmp_geometry.argtypes = [C.POINTER(avmp_config_t), C.c_size_t, C.POINTER(avmp_geometry_t)]
+lib.avmp_pools_create.argtypes = [C.POINTER(avmp_config_t), _P, C.c_size_t, C.POINTER(_P)]
+lib.avmp_pools_destroy.argtypes = [_P]
+lib.avmp_alloc.argtypes = [_P, C.c_int, C.c_uint32, _P]
+lib.avmp_free.argtypes = [_P, _P, C.c_uint32]
+lib.avmp_migrate.argtypes = [_P, C.c_int, C.c_uint32, _P, C.POINTER(avmp_migrate_result_t)]
+lib.avmp_decode_step.argtypes = [_P, C.POINTER(avmp_step_t), _P]
+lib.avmp_flush.argtypes = [_P, _P]
+lib.avmp_translate.argtypes = [_P, _P, C.c_uint32, _P, _P]
+lib.avmp_resolve.argtypes = [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                             C.POINTER(C.c_uint64)]
+lib.avmp_stats.argtypes = [_P, C.POINTER(avmp_stats_t)]
+lib.avmp_device_faults.argtypes = [_P, _P, C.POINTER(C.c_uint64)]
+for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_alloc", "avmp_free",
+           "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
+           "avmp_stats", "avmp_device_faults"):
+    getattr(lib, _f).restype = C.c_int
+
+
+def avmp_last_error() -> str:
+    return lib.avmp_last_error().decode()
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return int(t)
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if hasattr(s, "cuda_stream"):
+        return s.cuda_stream
+    return int(s)
+
+
+def make_config(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, ssm_heads: int,
+                ssm_headdim: int, ssm_dstate: int, kv_capacity: int, ssm_capacity: int,
+                slot_rank: Optional[Sequence[Optional[np.ndarray]]] = None,
+                max_vid: Sequence[int] = (0, 0), page_tokens: int = 16):
+    """Returns (avmp_config_t, keepalive): keepalive holds the rank arrays the struct points to."""
+    cfg = avmp_config_t()
+    cfg.dtype = AVMP_F32 if dtype == "f32" else AVMP_BF16
+    cfg.attention_page_tokens = page_tokens
+    cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_q_heads, n_kv_heads, head_dim
+    cfg.ssm_heads, cfg.ssm_headdim, cfg.ssm_dstate = ssm_heads, ssm_headdim, ssm_dstate
+    cfg.kv_capacity, cfg.ssm_capacity = kv_capacity, ssm_capacity
+    cfg.max_vid[0], cfg.max_vid[1] = max_vid
+    keep = []
+    for p in range(2):
+        r = None if slot_rank is None else slot_rank[p]
+        if r is None:
+            cfg.slot_rank[p] = C.POINTER(C.c_uint32)()
+        else:
+            a = np.ascontiguousarray(r, dtype=np.uint32)
+            keep.append(a)
+            cfg.slot_rank[p] = a.ctypes.data_as(C.POINTER(C.c_uint32))
+    return cfg, keep
+
+
+def avmp_geometry(cfg: avmp_config_t, arena_bytes: int):
+    g = avmp_geometry_t()
+    rc = lib.avmp_geometry(C.byref(cfg), arena_bytes, C.byref(g))
+    return rc, g
+
+
+def avmp_pools_create(cfg: avmp_config_t, arena, arena_bytes: int):
+    """arena: torch uint8 tensor on the device, an integer address, or None (metadata only)."""
+    out = _P()
+    rc = lib.avmp_pools_create(C.byref(cfg), _ptr(arena), arena_bytes, C.byref(out))
+    return rc, (out.value if rc == AVMP_OK else None)
+
+
+def avmp_pools_destroy(pools) -> int:
+    return lib.avmp_pools_destroy(pools)
+
+
+def avmp_alloc(pools, pool: int, n: int):
+    out = np.empty(max(n, 1), dtype=np.uint32)
+    rc = lib.avmp_alloc(pools, pool, n, out.ctypes.data)
+    return rc, (out[:n] if rc == AVMP_OK else None)
+
+
+def avmp_free(pools, handles) -> int:
+    h = np.ascontiguousarray(handles, dtype=np.uint32)
+    return lib.avmp_free(pools, h.ctypes.data, h.size)
+
+
+def avmp_migrate(pools, donor_pool: int, n_donor_units: int, stream=None):
+    res = avmp_migrate_result_t()
+    rc = lib.avmp_migrate(pools, donor_pool, n_donor_units, _stream(stream), C.byref(res))
+    return rc, res
+
+
+def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles, ctx, q, o,
+              ssm_handles, x, dt, A, B, Cm, y):
+    """Returns (avmp_step_t, keepalive).  Tensors must stay alive until the step has run."""
+    st = avmp_step_t()
+    kinds = np.ascontiguousarray(layer_kinds, dtype=np.uint8)
+    st.batch, st.n_layers, st.max_pages = batch, len(kinds), max_pages
+    st.layer_kind = kinds.ctypes.data
+    st.kv_handles, st.ctx, st.q, st.o = _ptr(kv_handles), _ptr(ctx), _ptr(q), _ptr(o)
+    st.ssm_handles, st.x, st.dt, st.A = _ptr(ssm_handles), _ptr(x), _ptr(dt), _ptr(A)
+    st.B, st.C, st.y = _ptr(B), _ptr(Cm), _ptr(y)
+    return st, (kinds, kv_handles, ctx, q, o, ssm_handles, x, dt, A, B, Cm, y)
+
+
+def avmp_decode_step(pools, step: avmp_step_t, stream=None) -> int:
+    return lib.avmp_decode_step(pools, C.byref(step), _stream(stream))
+
+
+def avmp_flush(pools, stream=None) -> int:
+    return lib.avmp_flush(pools, _stream(stream))
+
+
+def avmp_translate(pools, handles_dev, n: int, offsets_dev, stream=None) -> int:
+    return lib.avmp_translate(pools, _ptr(handles_dev), n, _ptr(offsets_dev), _stream(stream))
+
+
+def avmp_resolve(pools, handle: int):
+    pool, slot, off = C.c_uint32(), C.c_uint32(), C.c_uint64()
+    rc = lib.avmp_resolve(pools, int(handle), C.byref(pool), C.byref(slot), C.byref(off))
+    return rc, pool.value, slot.value, off.value
+
+
+def avmp_stats(pools) -> dict:
+    st = avmp_stats_t()
+    rc = lib.avmp_stats(pools, C.byref(st))
+    if rc != AVMP_OK:
+        raise RuntimeError(avmp_last_error())
+    return {"capacity": tuple(st.capacity), "live": tuple(st.live), "free": tuple(st.free_units),
+            "gap_bytes": st.gap_bytes, "ops": st.ops, "capacity_errors": st.capacity_errors,
+            "migrations": st.migrations, "units_copied": st.units_copied,
+            "bytes_migrated": st.bytes_migrated, "bytes_wasted": st.bytes_wasted}
+
+
+def avmp_device_faults(pools, stream=None):
+    out = C.c_uint64()
+    rc = lib.avmp_device_faults(pools, _stream(stream), C.byref(out))
+    return rc, out.value

@@ -1,0 +1,448 @@
+// C ABI of the library: glue between the host-side pool state, the device
+// table mirror and the kernels.  See include/avmp.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/avmp.h"
+#include "kernels.hpp"
+#include "pool_state.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* what) {
+  g_last_error = what;
+  return code;
+}
+
+int fail_hip(hipError_t e, const char* where) {
+  g_last_error = std::string(where) + ": " + hipGetErrorString(e);
+  return AVMP_ERR_DEVICE;
+}
+
+#define HIP_TRY(expr)                                \
+  do {                                               \
+    hipError_t e_ = (expr);                          \
+    if (e_ != hipSuccess) return fail_hip(e_, #expr); \
+  } while (0)
+
+// Pinned host buffers that kernels read directly (lists of table updates, slots
+// to clear, moves).  A buffer is reused only after the event recorded behind its
+// last consumer has completed, so the host never overwrites a list in flight.
+struct Staging {
+  struct Buf {
+    void* host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool busy = false;
+  };
+  std::vector<Buf> bufs;
+
+  hipError_t acquire(size_t bytes, Buf** out) {
+    for (auto& b : bufs) {
+      if (b.busy && hipEventQuery(b.ev) == hipSuccess) b.busy = false;
+      if (!b.busy && b.cap >= bytes) {
+        *out = &b;
+        return hipSuccess;
+      }
+    }
+    Buf b;
+    b.cap = bytes < (1u << 16) ? (1u << 16) : bytes;
+    hipError_t e = hipHostMalloc(&b.host, b.cap, hipHostMallocDefault);
+    if (e != hipSuccess) return e;
+    e = hipEventCreateWithFlags(&b.ev, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      (void)hipHostFree(b.host);
+      return e;
+    }
+    bufs.push_back(b);
+    *out = &bufs.back();
+    return hipSuccess;
+  }
+  hipError_t release_after(Buf* b, hipStream_t s) {
+    b->busy = true;
+    return hipEventRecord(b->ev, s);
+  }
+  void destroy() {
+    for (auto& b : bufs) {
+      if (b.busy) (void)hipEventSynchronize(b.ev);
+      (void)hipEventDestroy(b.ev);
+      (void)hipHostFree(b.host);
+    }
+    bufs.clear();
+  }
+};
+
+}  // namespace
+
+struct avmp_pools {
+  avmp_config_t cfg{};
+  avmp::PoolState st;
+  bool has_device = false;
+  uint8_t* arena = nullptr;
+  uint32_t* table_dev = nullptr;
+  unsigned long long* faults_dev = nullptr;
+  float* ws = nullptr;                 // attention chunk partials
+  size_t ws_bytes = 0;
+  std::vector<avmp::TableUpdate> pending;
+  std::vector<uint32_t> pending_zero;  // SSM slots to clear
+  Staging staging;
+
+  avmp::DevPools dev_view() const {
+    avmp::DevPools P{};
+    P.arena = arena;
+    P.usable = st.geometry().usable;
+    P.table = table_dev;
+    P.faults = faults_dev;
+    for (int p = 0; p < 2; ++p) {
+      P.unit[p] = st.geometry().unit[p];
+      P.vid_base[p] = st.vid_base(p);
+      P.max_vid[p] = st.max_vid(p);
+      P.capacity[p] = st.capacity(p);
+    }
+    return P;
+  }
+};
+
+namespace {
+
+bool shape_from_config(const avmp_config_t* c, avmp::ShapeArgs* s) {
+  if (c == nullptr) return false;
+  if (c->dtype != AVMP_F32 && c->dtype != AVMP_BF16) return false;
+  s->elem_bytes = c->dtype == AVMP_F32 ? 4 : 2;
+  if (c->attention_page_tokens != 16) return false;
+  if (c->n_kv_heads == 0 || c->n_q_heads == 0 || c->n_q_heads % c->n_kv_heads != 0) return false;
+  const uint32_t x = 16 / s->elem_bytes;
+  if (c->head_dim == 0 || c->head_dim % x != 0 || c->head_dim > 256) return false;
+  const uint32_t n = c->ssm_dstate;
+  if (n < 4 || n > 256 || (n & (n - 1)) != 0) return false;
+  if (c->ssm_heads == 0 || c->ssm_headdim == 0) return false;
+  if (c->ssm_heads > 65535 || c->n_q_heads > 65535) return false;
+  s->page_tokens = c->attention_page_tokens;
+  s->n_q_heads = c->n_q_heads;
+  s->n_kv_heads = c->n_kv_heads;
+  s->head_dim = c->head_dim;
+  s->ssm_heads = c->ssm_heads;
+  s->ssm_headdim = c->ssm_headdim;
+  s->ssm_dstate = c->ssm_dstate;
+  return true;
+}
+
+// Queue -> device: table entries (coalesced to the last value per index, so the
+// scatter has no ordering hazard) and zero fills of freshly allocated SSM blocks.
+int flush_pending(avmp_pools* p, hipStream_t s) {
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  if (p->pending.empty() && p->pending_zero.empty()) return AVMP_OK;
+  std::vector<avmp::TableUpdate> upd;
+  if (!p->pending.empty()) {
+    std::unordered_map<uint32_t, uint32_t> last;
+    last.reserve(p->pending.size() * 2);
+    for (const auto& u : p->pending) last[u.index] = u.slot;
+    upd.reserve(last.size());
+    for (const auto& kv : last) upd.push_back({kv.first, kv.second});
+  }
+  const size_t upd_bytes = upd.size() * sizeof(avmp::TableUpdate);
+  const size_t zero_bytes = p->pending_zero.size() * sizeof(uint32_t);
+  Staging::Buf* b = nullptr;
+  HIP_TRY(p->staging.acquire(upd_bytes + zero_bytes, &b));
+  char* host = static_cast<char*>(b->host);
+  if (upd_bytes) std::memcpy(host, upd.data(), upd_bytes);
+  if (zero_bytes) std::memcpy(host + upd_bytes, p->pending_zero.data(), zero_bytes);
+  HIP_TRY(avmp::launch_table_updates(p->table_dev, reinterpret_cast<const avmp::TableUpdate*>(host),
+                                     uint32_t(upd.size()), s));
+  HIP_TRY(avmp::launch_zero_units(p->dev_view(), AVMP_POOL_SSM,
+                                  reinterpret_cast<const uint32_t*>(host + upd_bytes),
+                                  uint32_t(p->pending_zero.size()), s));
+  HIP_TRY(p->staging.release_after(b, s));
+  p->pending.clear();
+  p->pending_zero.clear();
+  return AVMP_OK;
+}
+
+int ensure_workspace(avmp_pools* p, size_t bytes) {
+  if (bytes <= p->ws_bytes) return AVMP_OK;
+  if (p->ws) {
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipFree(p->ws));
+    p->ws = nullptr;
+    p->ws_bytes = 0;
+  }
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->ws), bytes));
+  p->ws_bytes = bytes;
+  return AVMP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* avmp_last_error(void) { return g_last_error.c_str(); }
+
+int avmp_geometry(const avmp_config_t* cfg, size_t arena_bytes, avmp_geometry_t* out) {
+  avmp::ShapeArgs s{};
+  avmp::Geometry g{};
+  if (out == nullptr || !shape_from_config(cfg, &s) || !avmp::compute_geometry(s, arena_bytes, &g))
+    return fail(AVMP_ERR_INVALID_ARG, "unsupported shape or arena size");
+  out->unit_bytes[0] = g.unit[0];
+  out->unit_bytes[1] = g.unit[1];
+  out->usable_bytes = g.usable;
+  out->max_slots[0] = g.max_slots[0];
+  out->max_slots[1] = g.max_slots[1];
+  return AVMP_OK;
+}
+
+int avmp_pools_create(const avmp_config_t* cfg, void* arena_dev, size_t arena_bytes,
+                      avmp_pools_t** out) {
+  avmp::ShapeArgs s{};
+  avmp::Geometry g{};
+  if (out == nullptr || !shape_from_config(cfg, &s) || !avmp::compute_geometry(s, arena_bytes, &g))
+    return fail(AVMP_ERR_INVALID_ARG, "unsupported shape or arena size");
+  if (arena_dev != nullptr && (reinterpret_cast<uintptr_t>(arena_dev) & 127u) != 0)
+    return fail(AVMP_ERR_INVALID_ARG, "arena must be 128-byte aligned");
+  avmp_pools* p = new (std::nothrow) avmp_pools();
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "out of host memory");
+  p->cfg = *cfg;
+  const uint32_t* ranks[2] = {cfg->slot_rank[0], cfg->slot_rank[1]};
+  if (!p->st.init(g, cfg->kv_capacity, cfg->ssm_capacity, cfg->max_vid, ranks)) {
+    delete p;
+    return fail(AVMP_ERR_INVALID_ARG,
+                "capacities do not fit the arena, or slot_rank is not a permutation");
+  }
+  p->cfg.slot_rank[0] = p->cfg.slot_rank[1] = nullptr;
+  if (arena_dev != nullptr) {
+    p->arena = static_cast<uint8_t*>(arena_dev);
+    const size_t entries = size_t(p->st.max_vid(0)) + p->st.max_vid(1);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->table_dev), entries * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemset(p->table_dev, 0xFF, entries * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->faults_dev), sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(p->faults_dev, 0, sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      if (p->table_dev) (void)hipFree(p->table_dev);
+      if (p->faults_dev) (void)hipFree(p->faults_dev);
+      delete p;
+      return fail_hip(e, "avmp_pools_create");
+    }
+    p->has_device = true;
+  }
+  *out = p;
+  return AVMP_OK;
+}
+
+int avmp_pools_destroy(avmp_pools_t* p) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  if (p->has_device) {
+    (void)hipDeviceSynchronize();
+    p->staging.destroy();
+    if (p->ws) (void)hipFree(p->ws);
+    (void)hipFree(p->table_dev);
+    (void)hipFree(p->faults_dev);
+  }
+  delete p;
+  return AVMP_OK;
+}
+
+int avmp_alloc(avmp_pools_t* p, int pool, uint32_t n, avmp_handle_t* out) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  // a request larger than the pool is refused before any handle is written
+  const size_t room = (pool == 0 || pool == 1) ? p->st.capacity(pool) : 0;
+  std::vector<uint32_t> tmp((n < room ? n : room) + 1);
+  const size_t upd0 = p->pending.size(), zero0 = p->pending_zero.size();
+  const int rc = p->st.alloc(pool, n, out ? tmp.data() : nullptr, &p->pending, &p->pending_zero);
+  if (rc != AVMP_OK) {
+    p->pending.resize(upd0);
+    p->pending_zero.resize(zero0);
+    return fail(rc, rc == AVMP_ERR_CAPACITY ? "pool is full" : "bad pool, n or out");
+  }
+  std::memcpy(out, tmp.data(), size_t(n) * sizeof(uint32_t));
+  if (!p->has_device) {
+    p->pending.clear();
+    p->pending_zero.clear();
+  }
+  return AVMP_OK;
+}
+
+int avmp_free(avmp_pools_t* p, const avmp_handle_t* handles, uint32_t n) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  const int rc = p->st.free_units(handles, n, &p->pending);
+  if (rc != AVMP_OK) return fail(rc, rc == AVMP_ERR_INVALID_HANDLE ? "stale or malformed handle" : "bad n");
+  if (!p->has_device) p->pending.clear();
+  return AVMP_OK;
+}
+
+int avmp_flush(avmp_pools_t* p, void* stream) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  return flush_pending(p, static_cast<hipStream_t>(stream));
+}
+
+int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migrate_result_t* out) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->has_device && (donor == 0 || donor == 1) && n != 0) {
+    // queued zero fills and table entries refer to the geometry before the move
+    const int rc = flush_pending(p, s);
+    if (rc != AVMP_OK) return rc;
+  }
+  std::vector<avmp::Move> moves;
+  std::vector<avmp::TableUpdate> remap;     // the copy kernel rewrites these entries itself
+  uint32_t gain = 0;
+  uint64_t wasted = 0;
+  const int rc = p->st.migrate(donor, n, &moves, &remap, &gain, &wasted);
+  if (rc != AVMP_OK)
+    return fail(rc, rc == AVMP_ERR_CAPACITY ? "donor has too few free units" : "bad donor or n");
+  if (p->has_device && !moves.empty()) {
+    const size_t bytes = moves.size() * sizeof(avmp::Move);
+    Staging::Buf* b = nullptr;
+    HIP_TRY(p->staging.acquire(bytes, &b));
+    std::memcpy(b->host, moves.data(), bytes);
+    // capacities in the view are already the new ones; the copy needs none of them
+    HIP_TRY(avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor,
+                                      static_cast<const avmp::Move*>(b->host),
+                                      uint32_t(moves.size()), s));
+    HIP_TRY(p->staging.release_after(b, s));
+  }
+  if (out) {
+    out->units_copied = uint32_t(moves.size());
+    out->recipient_gain = gain;
+    out->bytes_wasted = wasted;
+  }
+  return AVMP_OK;
+}
+
+int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
+  if (p == nullptr || st == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  if (st->n_layers != 0 && st->layer_kind == nullptr) return fail(AVMP_ERR_INVALID_ARG, "layer_kind");
+  uint32_t n_attn = 0, n_ssm = 0;
+  for (uint32_t i = 0; i < st->n_layers; ++i) {
+    if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) ++n_attn;
+    else if (st->layer_kind[i] == AVMP_LAYER_SSM) ++n_ssm;
+    else return fail(AVMP_ERR_INVALID_ARG, "unknown layer kind");
+  }
+  if (st->batch > 65535) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
+  if (n_attn && st->batch &&
+      (!st->kv_handles || !st->ctx || !st->q || !st->o || st->max_pages == 0))
+    return fail(AVMP_ERR_INVALID_ARG, "attention layers need kv_handles, ctx, q, o, max_pages");
+  if (n_ssm && st->batch &&
+      (!st->ssm_handles || !st->x || !st->dt || !st->A || !st->B || !st->C || !st->y))
+    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need ssm_handles, x, dt, A, B, C, y");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = flush_pending(p, s);
+  if (rc != AVMP_OK) return rc;
+  if (st->batch == 0) return AVMP_OK;
+
+  const avmp_config_t& c = p->cfg;
+  const size_t eb = c.dtype == AVMP_F32 ? 4 : 2;
+  const uint32_t worst = (st->max_pages + avmp::kChunkPages - 1) / avmp::kChunkPages;
+  const uint32_t max_chunks = worst < avmp::kMaxChunks ? worst : avmp::kMaxChunks;
+  const size_t part_rows = size_t(st->batch) * max_chunks * c.n_q_heads;
+  if (n_attn) {
+    rc = ensure_workspace(p, part_rows * (size_t(c.head_dim) + 2) * sizeof(float));
+    if (rc != AVMP_OK) return rc;
+  }
+  const avmp::DevPools P = p->dev_view();
+  uint32_t ia = 0, is = 0;
+  for (uint32_t i = 0; i < st->n_layers; ++i) {
+    if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) {
+      avmp::AttnLaunch a{};
+      a.P = P;
+      a.handles = st->kv_handles + size_t(ia) * st->batch * st->max_pages;
+      a.ctx = st->ctx;
+      const size_t row = size_t(st->batch) * c.n_q_heads * c.head_dim;
+      a.q = static_cast<const char*>(st->q) + size_t(ia) * row * eb;
+      a.o = st->o + size_t(ia) * row;
+      a.part_o = p->ws;
+      a.part_ml = p->ws + part_rows * c.head_dim;
+      a.batch = st->batch;
+      a.max_pages = st->max_pages;
+      a.max_chunks = max_chunks;
+      a.n_q_heads = c.n_q_heads;
+      a.n_kv_heads = c.n_kv_heads;
+      a.head_dim = c.head_dim;
+      a.dtype = c.dtype;
+      HIP_TRY(avmp::launch_attention(a, s));
+      ++ia;
+    } else {
+      avmp::SsmLaunch a{};
+      a.P = P;
+      a.handles = st->ssm_handles + size_t(is) * st->batch;
+      const size_t xrow = size_t(st->batch) * c.ssm_heads * c.ssm_headdim;
+      a.x = static_cast<const char*>(st->x) + size_t(is) * xrow * eb;
+      a.dt = st->dt + size_t(is) * st->batch * c.ssm_heads;
+      a.A = st->A + size_t(is) * c.ssm_heads;
+      a.B = static_cast<const char*>(st->B) + size_t(is) * st->batch * c.ssm_dstate * eb;
+      a.C = static_cast<const char*>(st->C) + size_t(is) * st->batch * c.ssm_dstate * eb;
+      a.y = st->y + size_t(is) * xrow;
+      a.batch = st->batch;
+      a.heads = c.ssm_heads;
+      a.headdim = c.ssm_headdim;
+      a.dstate = c.ssm_dstate;
+      a.dtype = c.dtype;
+      HIP_TRY(avmp::launch_ssm(a, s));
+      ++is;
+    }
+  }
+  return AVMP_OK;
+}
+
+int avmp_translate(avmp_pools_t* p, const avmp_handle_t* handles_dev, uint32_t n,
+                   uint64_t* offsets_dev, void* stream) {
+  if (p == nullptr || (n && (!handles_dev || !offsets_dev)))
+    return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int rc = flush_pending(p, s);
+  if (rc != AVMP_OK) return rc;
+  HIP_TRY(avmp::launch_translate(p->dev_view(), handles_dev, n, offsets_dev, s));
+  return AVMP_OK;
+}
+
+int avmp_resolve(const avmp_pools_t* p, avmp_handle_t h, uint32_t* pool, uint32_t* slot,
+                 uint64_t* byte_off) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  uint32_t pl, sl;
+  uint64_t off;
+  if (!p->st.resolve(h, &pl, &sl, &off)) return fail(AVMP_ERR_INVALID_HANDLE, "not a live handle");
+  if (pool) *pool = pl;
+  if (slot) *slot = sl;
+  if (byte_off) *byte_off = off;
+  return AVMP_OK;
+}
+
+int avmp_stats(const avmp_pools_t* p, avmp_stats_t* out) {
+  if (p == nullptr || out == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  const avmp::Counters& c = p->st.counters();
+  for (int i = 0; i < 2; ++i) {
+    out->capacity[i] = p->st.capacity(i);
+    out->live[i] = p->st.live(i);
+    out->free_units[i] = p->st.capacity(i) - p->st.live(i);
+  }
+  out->gap_bytes = p->st.gap();
+  out->ops = c.ops;
+  out->capacity_errors = c.capacity_errors;
+  out->migrations = c.migrations;
+  out->units_copied = c.units_copied;
+  out->bytes_migrated = c.bytes_migrated;
+  out->bytes_wasted = c.bytes_wasted;
+  return AVMP_OK;
+}
+
+int avmp_device_faults(avmp_pools_t* p, void* stream, uint64_t* out) {
+  if (p == nullptr || out == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipStreamSynchronize(s));
+  unsigned long long v = 0;
+  HIP_TRY(hipMemcpy(&v, p->faults_dev, sizeof(v), hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemset(p->faults_dev, 0, sizeof(v)));
+  *out = v;
+  return AVMP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Device-side view of the pools and handle translation (Fig. 1: the handle's
+// pool tag selects the store, its page id indexes the table, the table entry
+// is the physical slot).  Shared by every kernel; passed by value at launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace avmp {
+
+struct DevPools {
+  uint8_t* arena;                 // 128-byte aligned base
+  uint64_t usable;                // SSM slots count down from arena + usable
+  const uint32_t* table;          // [max_vid[0] + max_vid[1]]: vid -> slot, 0xFFFFFFFF unmapped
+  unsigned long long* faults;     // handles that did not translate
+  uint64_t unit[2];
+  uint32_t vid_base[2];
+  uint32_t max_vid[2];
+  uint32_t capacity[2];
+};
+
+constexpr uint32_t kDevUnmapped = 0xFFFFFFFFu;
+
+// handle -> byte offset from the arena base, or ~0 if the handle does not name a
+// live unit of `want_pool`.  Every check is on values, so a bad handle can never
+// produce an address outside the arena.
+__device__ __forceinline__ uint64_t translate_offset(const DevPools& P, uint32_t h,
+                                                     uint32_t want_pool) {
+  const uint32_t pool = h >> 30, vid = h & 0x3FFFFFFFu;
+  if (pool != want_pool || vid >= P.max_vid[want_pool]) return ~0ull;
+  const uint32_t slot = P.table[P.vid_base[want_pool] + vid];
+  if (slot >= P.capacity[want_pool]) return ~0ull;       // also catches 0xFFFFFFFF
+  return want_pool == 0 ? uint64_t(slot) * P.unit[0]
+                        : P.usable - (uint64_t(slot) + 1) * P.unit[1];
+}
+
+__device__ __forceinline__ void count_fault(const DevPools& P) { atomicAdd(P.faults, 1ull); }
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) {
+  return __uint_as_float(b << 16);
+}
+
+template <typename E>
+__device__ __forceinline__ float load_elem(const E* p);
+template <>
+__device__ __forceinline__ float load_elem<float>(const float* p) {
+  return *p;
+}
+template <>
+__device__ __forceinline__ float load_elem<uint16_t>(const uint16_t* p) {
+  return bf16_bits_to_float(*p);
+}
+
+// Split of a request's pages into chunks processed by different wavefronts and
+// merged afterwards.  It depends on the request's page count only, never on
+// physical placement, so results are identical under any placement and across
+// migrations.  Short requests use kChunkPages-page chunks; long ones use larger
+// chunks so that no request has more than kMaxChunks of them.
+constexpr uint32_t kChunkPages = 8;
+constexpr uint32_t kMaxChunks = 64;
+
+__host__ __device__ __forceinline__ uint32_t chunk_pages_for(uint32_t n_pages) {
+  const uint32_t span = kChunkPages * kMaxChunks;
+  return kChunkPages * ((n_pages + span - 1) / span);
+}
+__host__ __device__ __forceinline__ uint32_t chunk_count_for(uint32_t n_pages) {
+  if (n_pages == 0) return 0;
+  const uint32_t cp = chunk_pages_for(n_pages);
+  return (n_pages + cp - 1) / cp;
+}
+
+}  // namespace avmp

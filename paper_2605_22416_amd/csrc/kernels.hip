@@ -1,0 +1,351 @@
+// gfx950 kernels of the hybrid decode path: table maintenance, translation,
+// shape-generic paged GQA decode attention (vector ALU), the chunk merge, the
+// in-place SSM state update and the migration copy + remap.
+#include "kernels.hpp"
+
+#include <cmath>
+
+namespace avmp {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------
+// table maintenance
+// ---------------------------------------------------------------------------
+__global__ void table_update_kernel(uint32_t* __restrict__ table,
+                                    const TableUpdate* __restrict__ upd, uint32_t n) {
+  // Updates are applied in list order per index: one thread walks nothing but
+  // its own entry, and the host never queues two updates of one index in one
+  // batch without ordering them (it coalesces to the last value first).
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) table[upd[i].index] = upd[i].slot;
+}
+
+__global__ __launch_bounds__(256) void zero_units_kernel(DevPools P, int pool,
+                                                         const uint32_t* __restrict__ slots) {
+  const uint32_t slot = slots[blockIdx.y];
+  if (slot >= P.capacity[pool]) return;     // freed and migrated away before the flush
+  const uint64_t off = pool == 0 ? uint64_t(slot) * P.unit[0]
+                                 : P.usable - (uint64_t(slot) + 1) * P.unit[1];
+  uint4* dst = reinterpret_cast<uint4*>(P.arena + off);
+  const uint64_t n16 = P.unit[pool] / 16;
+  const uint4 z = make_uint4(0, 0, 0, 0);
+  for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += uint64_t(gridDim.x) * 256)
+    dst[i] = z;
+}
+
+__global__ void translate_kernel(DevPools P, const uint32_t* __restrict__ handles, uint32_t n,
+                                 uint64_t* __restrict__ out) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t h = handles[i];
+  const uint32_t pool = h >> 30;
+  out[i] = pool < 2 ? translate_offset(P, h, pool) : ~0ull;
+}
+
+// ---------------------------------------------------------------------------
+// migration: copy each live unit out of the vacated range, then point its
+// table entry at the new slot (Method, "Dynamic Pool Rebalancing"; the copy is
+// what a single arena needs in place of the prototype's oversized tensors).
+// Source slots lie at or above the new capacity and destinations below it, so
+// no two copies overlap.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t* __restrict__ table,
+                                                           int pool, const Move* __restrict__ moves) {
+  const Move mv = moves[blockIdx.y];
+  const uint64_t unit = P.unit[pool];
+  const uint64_t so = pool == 0 ? uint64_t(mv.src_slot) * unit : P.usable - (uint64_t(mv.src_slot) + 1) * unit;
+  const uint64_t dof = pool == 0 ? uint64_t(mv.dst_slot) * unit : P.usable - (uint64_t(mv.dst_slot) + 1) * unit;
+  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(P.arena + so);
+  uint4* __restrict__ dst = reinterpret_cast<uint4*>(P.arena + dof);
+  const uint64_t n16 = unit / 16;
+  const uint64_t stride = uint64_t(gridDim.x) * 256;
+  uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x;
+  // four independent 16-byte loads in flight per lane
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
+  if (blockIdx.x == 0 && threadIdx.x == 0) table[P.vid_base[pool] + mv.vid] = mv.dst_slot;
+}
+
+// ---------------------------------------------------------------------------
+// shape-generic paged GQA decode attention: one wavefront per (query head,
+// chunk, request).  Lane = (token t = lane%16, dim quarter = lane/16) for the
+// scores; lane = dim for the weighted sum of V.  Online softmax in the log2
+// domain, fp32 throughout.  Used for fp32 pools and for head shapes the
+// matrix-core kernel does not take.
+// ---------------------------------------------------------------------------
+// Tokens of request r that the handle row can cover: a context longer than
+// max_pages pages is the caller's mistake; it is clamped (and counted as a
+// fault by the merge kernel) so that the handle row is never read past its end.
+__device__ __forceinline__ uint32_t resident_tokens(const AttnLaunch& a, uint32_t r) {
+  const uint32_t n = a.ctx[r];
+  const uint64_t room = uint64_t(a.max_pages) * 16u;
+  return n > room ? uint32_t(room) : n;
+}
+
+template <typename E>
+__global__ __launch_bounds__(64) void attn_generic_kernel(AttnLaunch a) {
+  const uint32_t j = blockIdx.x, c = blockIdx.y, r = blockIdx.z;
+  const uint32_t lane = threadIdx.x;
+  const uint32_t n_tok = resident_tokens(a, r);
+  const uint32_t n_pages = (n_tok + 15) / 16;
+  const uint32_t nch = chunk_count_for(n_pages);
+  if (c >= nch) return;
+  const uint32_t cp = chunk_pages_for(n_pages);
+  const uint32_t p0 = c * cp;
+  const uint32_t p1 = min(n_pages, p0 + cp);
+  const uint32_t D = a.head_dim, G = a.n_kv_heads, Hq = a.n_q_heads;
+  const uint32_t g = j / (Hq / G);
+  constexpr uint32_t X = 16 / sizeof(E);
+
+  __shared__ float qs[256];
+  const E* qrow = static_cast<const E*>(a.q) + (size_t(r) * Hq + j) * D;
+  for (uint32_t d = lane; d < D; d += 64) qs[d] = load_elem<E>(qrow + d);
+  __syncthreads();
+
+  const float scale_log2 = kLog2e / sqrtf(float(D));
+  const uint32_t t = lane & 15, dq = lane >> 4;
+  const uint32_t DQ = D / 4;
+  float m = -INFINITY, l = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+
+  for (uint32_t page = p0; page < p1; ++page) {
+    const uint32_t h = a.handles[size_t(r) * a.max_pages + page];
+    const uint64_t off = translate_offset(a.P, h, 0);
+    if (off == ~0ull) {                         // wave-uniform: skip the page, count it
+      if (lane == 0) count_fault(a.P);
+      continue;
+    }
+    const E* pg = reinterpret_cast<const E*>(a.P.arena + off);
+    const uint32_t n_valid = min(16u, n_tok - page * 16);
+    const E* kbase = pg + size_t(g) * D * 16;                       // [D/X][16][X]
+    float s = 0.f;
+    for (uint32_t d = dq * DQ; d < (dq + 1) * DQ; ++d)
+      s += qs[d] * load_elem<E>(kbase + ((d / X) * 16 + t) * X + d % X);
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    s = (t < n_valid) ? s * scale_log2 : -INFINITY;                 // tail slots never count
+    float pm = s;
+    for (int o = 8; o; o >>= 1) pm = fmaxf(pm, __shfl_xor(pm, o));
+    const float m_new = fmaxf(m, pm);
+    const float alpha = exp2f(m - m_new);
+    const float p = exp2f(s - m_new);
+    float ps = p;
+    for (int o = 8; o; o >>= 1) ps += __shfl_xor(ps, o);
+    l = l * alpha + ps;
+    m = m_new;
+    const E* vbase = pg + size_t(G) * 16 * D + size_t(g) * D * 16;  // [D][16]
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] *= alpha;
+    for (uint32_t tt = 0; tt < n_valid; ++tt) {
+      const float pt = __shfl(p, int(tt));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t d = lane + 64 * i;
+        if (d < D) acc[i] += pt * load_elem<E>(vbase + size_t(d) * 16 + tt);
+      }
+    }
+  }
+
+  if (nch == 1) {
+    float* orow = a.o + (size_t(r) * Hq + j) * D;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t d = lane + 64 * i;
+      if (d < D) orow[d] = l > 0.f ? acc[i] / l : 0.f;
+    }
+  } else {
+    const size_t idx = (size_t(r) * a.max_chunks + c) * Hq + j;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t d = lane + 64 * i;
+      if (d < D) a.part_o[idx * D + d] = acc[i];
+    }
+    if (lane == 0) {
+      a.part_ml[idx * 2] = m;
+      a.part_ml[idx * 2 + 1] = l;
+    }
+  }
+}
+
+// Merge of per-chunk partial results in logical chunk order (so the result is a
+// function of the logical batch alone).  One wavefront per (query head, request).
+__global__ __launch_bounds__(64) void attn_merge_kernel(AttnLaunch a) {
+  const uint32_t j = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+  if (j == 0 && lane == 0 && uint64_t(a.ctx[r]) > uint64_t(a.max_pages) * 16u) count_fault(a.P);
+  const uint32_t n_pages = (resident_tokens(a, r) + 15) / 16;
+  const uint32_t nch = chunk_count_for(n_pages);
+  const uint32_t D = a.head_dim, Hq = a.n_q_heads;
+  float* orow = a.o + (size_t(r) * Hq + j) * D;
+  if (nch == 0) {
+    for (uint32_t d = lane; d < D; d += 64) orow[d] = 0.f;
+    return;
+  }
+  if (nch == 1) return;            // written directly by the attention kernel
+  const size_t base = (size_t(r) * a.max_chunks) * Hq + j;
+  float M = -INFINITY;
+  for (uint32_t c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[(base + size_t(c) * Hq) * 2]);
+  float L = 0.f;
+  for (uint32_t c = 0; c < nch; ++c) {
+    const size_t idx = base + size_t(c) * Hq;
+    L += a.part_ml[idx * 2 + 1] * exp2f(a.part_ml[idx * 2] - M);
+  }
+  for (uint32_t d = lane; d < D; d += 64) {
+    float sum = 0.f;
+    for (uint32_t c = 0; c < nch; ++c) {
+      const size_t idx = base + size_t(c) * Hq;
+      sum += a.part_o[idx * D + d] * exp2f(a.part_ml[idx * 2] - M);
+    }
+    orow[d] = L > 0.f ? sum / L : 0.f;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// SSM single-token state update, in place.  One workgroup per (head, request):
+// the head's [P][N] fp32 tile is streamed once in and once out with 16-byte
+// accesses; a row's N values sit in N/4 adjacent lanes, which also reduce
+// y = sum_n S*C.  ROWS independent 16-byte loads are in flight per lane.
+// ---------------------------------------------------------------------------
+template <typename E>
+__device__ __forceinline__ float4 load4(const E* p);
+template <>
+__device__ __forceinline__ float4 load4<float>(const float* p) {
+  return *reinterpret_cast<const float4*>(p);
+}
+template <>
+__device__ __forceinline__ float4 load4<uint16_t>(const uint16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u),
+                     __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
+}
+
+template <typename E, int ROWS>
+__global__ __launch_bounds__(256) void ssm_update_kernel(SsmLaunch a) {
+  const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+  const uint32_t H = a.heads, Pd = a.headdim, N = a.dstate;
+  const uint64_t off = translate_offset(a.P, a.handles[r], 1);
+  float* yrow = a.y + (size_t(r) * H + h) * Pd;
+  if (off == ~0ull) {
+    if (tid == 0) count_fault(a.P);
+    for (uint32_t p = tid; p < Pd; p += 256) yrow[p] = 0.f;
+    return;
+  }
+  const uint32_t lpr = N / 4;                  // lanes per row (power of two, <= 64)
+  const uint32_t col = tid & (lpr - 1);
+  const uint32_t row0 = tid / lpr;
+  const uint32_t rpi = 256 / lpr;              // rows per pass of the workgroup
+  const float dt = a.dt[size_t(r) * H + h];
+  const float decay = expf(dt * a.A[h]);
+  const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
+  const float4 Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
+  const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
+  float* S = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N + 4 * col;
+
+  for (uint32_t pbase = row0; pbase < Pd; pbase += rpi * ROWS) {
+    float4 s[ROWS];
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+      const uint32_t p = pbase + k * rpi;
+      if (p < Pd) s[k] = *reinterpret_cast<const float4*>(S + size_t(p) * N);
+    }
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+      const uint32_t p = pbase + k * rpi;
+      if (p < Pd) {
+        const float dtx = dt * load_elem<E>(xrow + p);
+        float4 v = s[k];
+        v.x = decay * v.x + dtx * Bv.x;
+        v.y = decay * v.y + dtx * Bv.y;
+        v.z = decay * v.z + dtx * Bv.z;
+        v.w = decay * v.w + dtx * Bv.w;
+        *reinterpret_cast<float4*>(S + size_t(p) * N) = v;
+        s[k] = v;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+      const uint32_t p = pbase + k * rpi;
+      // p < Pd is uniform over the lpr lanes of a row, and rows never straddle
+      // a 64-lane wavefront, but shuffle on all lanes anyway and mask the store
+      float part = 0.f;
+      if (p < Pd) part = s[k].x * Cv.x + s[k].y * Cv.y + s[k].z * Cv.z + s[k].w * Cv.w;
+      for (uint32_t o = lpr >> 1; o; o >>= 1) part += __shfl_xor(part, int(o));
+      if (p < Pd && col == 0) yrow[p] = part;
+    }
+  }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+hipError_t launch_table_updates(uint32_t* table, const TableUpdate* upd, uint32_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  table_update_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(table, upd, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero_units(const DevPools& P, int pool, const uint32_t* slots, uint32_t n,
+                             hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const uint64_t n16 = P.unit[pool] / 16;
+  uint32_t gx = uint32_t((n16 + 256 * 8 - 1) / (256 * 8));
+  if (gx == 0) gx = 1;
+  for (uint32_t done = 0; done < n; done += 65535) {
+    const uint32_t cnt = n - done < 65535 ? n - done : 65535;
+    zero_units_kernel<<<dim3(gx, cnt), dim3(256), 0, s>>>(P, pool, slots + done);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_migrate_copy(const DevPools& P, uint32_t* table, int pool, const Move* moves,
+                               uint32_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const uint64_t n16 = P.unit[pool] / 16;
+  uint32_t gx = uint32_t((n16 + 256 * 4 - 1) / (256 * 4));    // 16 KiB per workgroup
+  if (gx == 0) gx = 1;
+  for (uint32_t done = 0; done < n; done += 65535) {
+    const uint32_t cnt = n - done < 65535 ? n - done : 65535;
+    migrate_copy_kernel<<<dim3(gx, cnt), dim3(256), 0, s>>>(P, table, pool, moves + done);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_translate(const DevPools& P, const uint32_t* handles, uint32_t n, uint64_t* out,
+                            hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  translate_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(P, handles, n, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
+  if (a.batch == 0) return hipSuccess;
+  const dim3 grid(a.n_q_heads, a.max_chunks, a.batch);
+  if (a.dtype == 0)
+    attn_generic_kernel<float><<<grid, dim3(64), 0, s>>>(a);
+  else
+    attn_generic_kernel<uint16_t><<<grid, dim3(64), 0, s>>>(a);
+  attn_merge_kernel<<<dim3(a.n_q_heads, a.batch), dim3(64), 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
+  if (a.batch == 0) return hipSuccess;
+  const dim3 grid(a.heads, a.batch);
+  if (a.dtype == 0)
+    ssm_update_kernel<float, 8><<<grid, dim3(256), 0, s>>>(a);
+  else
+    ssm_update_kernel<uint16_t, 8><<<grid, dim3(256), 0, s>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace avmp

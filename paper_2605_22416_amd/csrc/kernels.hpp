@@ -1,0 +1,49 @@
+// Launchers of the gfx950 kernels.  Each returns the hipError_t of its launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "device_common.hpp"
+#include "pool_state.hpp"
+
+namespace avmp {
+
+struct AttnLaunch {
+  DevPools P;
+  const uint32_t* handles;   // device [batch][max_pages] of this layer
+  const uint32_t* ctx;       // device [batch]
+  const void* q;             // device [batch][Hq][D]
+  float* o;                  // device [batch][Hq][D]
+  float* part_o;             // device [batch][max_chunks][Hq][D]
+  float* part_ml;            // device [batch][max_chunks][Hq][2]
+  uint32_t batch, max_pages, max_chunks;
+  uint32_t n_q_heads, n_kv_heads, head_dim;
+  uint32_t dtype;            // 0 f32, 1 bf16
+};
+
+struct SsmLaunch {
+  DevPools P;
+  const uint32_t* handles;   // device [batch]
+  const void* x;             // device [batch][H][P]
+  const float* dt;           // device [batch][H]
+  const float* A;            // device [H]
+  const void* B;             // device [batch][N]
+  const void* C;             // device [batch][N]
+  float* y;                  // device [batch][H][P]
+  uint32_t batch, heads, headdim, dstate;
+  uint32_t dtype;
+};
+
+hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
+hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s);
+hipError_t launch_table_updates(uint32_t* table, const TableUpdate* upd, uint32_t n, hipStream_t s);
+hipError_t launch_zero_units(const DevPools& P, int pool, const uint32_t* slots, uint32_t n,
+                             hipStream_t s);
+hipError_t launch_migrate_copy(const DevPools& P, uint32_t* table, int pool, const Move* moves,
+                               uint32_t n, hipStream_t s);
+hipError_t launch_translate(const DevPools& P, const uint32_t* handles, uint32_t n, uint64_t* out,
+                            hipStream_t s);
+
+}  // namespace avmp
