@@ -21,7 +21,35 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(
         "native library %s is missing: build it with `python -m paper_2605_22416_amd.build` "
         "(there is no CPU fallback)" % LIB_PATH)
-lib = C.CDLL(LIB_PATH)
+
+
+def _load():
+    """Load libavmp.so against the HIP runtime that torch has already loaded.
+
+    The caller's device memory and streams come from torch, so the library must
+    talk to the same runtime instance.  torch ships its own libamdhip64 (same
+    soname as the system one); importing torch first makes the loader resolve
+    libavmp's dependency to that instance.  Two runtimes in one process cannot
+    share pointers, so that case is refused."""
+    import torch  # noqa: F401
+    tlib = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if os.path.exists(tlib):
+        C.CDLL(tlib, mode=C.RTLD_GLOBAL)
+    handle = C.CDLL(LIB_PATH)
+    runtimes = set()
+    with open("/proc/self/maps") as f:
+        for line in f:
+            path = line.split()[-1]
+            if "libamdhip64" in os.path.basename(path):
+                runtimes.add(os.path.realpath(path))
+    if len(runtimes) > 1:
+        raise ImportError("two HIP runtimes are loaded in this process (%s): import "
+                          "paper_2605_22416_amd.binding before anything else loads libamdhip64"
+                          % ", ".join(sorted(runtimes)))
+    return handle
+
+
+lib = _load()
 
 AVMP_OK, AVMP_ERR_CAPACITY, AVMP_ERR_INVALID_HANDLE, AVMP_ERR_INVALID_ARG, AVMP_ERR_DEVICE = range(5)
 AVMP_POOL_KV, AVMP_POOL_SSM = 0, 1

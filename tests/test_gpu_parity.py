@@ -93,7 +93,7 @@ def test_tiny_fp32_step_then_migrate_four_pages_and_rerun():
                 (ores.units_copied, 8, 0)
             assert av.avmp_stats(g.p) == op.stats()
             assert av.avmp_stats(g.p)["capacity"] == (60, 16)
-        _check_translation(g, op, list(kv.reshape(-1)) + list(ssm.reshape(-1)) + [0xFFFFFFFF, 5 << 30])
+        _check_translation(g, op, list(kv.reshape(-1)) + list(ssm.reshape(-1)) + [0xFFFFFFFF, (2 << 30) | 5])
         ref_o, ref_y = _oracle_step(op, sc, kv, ssm, inp)
         o, y = g.step(inp)
         _check_outputs(spec, o, y, ref_o, ref_y, "tiny migrate=%s" % migrate)
