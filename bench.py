@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid decode path on one MI355X.
+
+Workload: the Jamba-mini-like decode step (4 attention + 28 SSM layers, bf16 in
+/ fp32 accumulate, 32 query / 8 KV heads x 128, 16-token pages, SSM 128 heads x
+64 x 128, batch 64, contexts uniform in [128, 2048], pools sized to 1.2x demand
+with seeded random placement).  One timed step is one pass of the whole path:
+  churn      one request's worth of handles is freed and re-allocated
+             (4 x 68 KV pages + 28 SSM blocks), table updates flushed on-stream
+  decode     translation + paged GQA attention + SSM update for all 32 layers
+  migration  128 KV pages of capacity (the paper's default batch) move to the
+             SSM pool and back, with live pages copied and the table rewritten
+Inputs are resident in HBM before the timed region.  The value reported is the
+algorithmic bytes of a step divided by the time of a step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def attention_bytes(spec, ctx):
+    """Algorithmic bytes of one attention layer for one request: valid K/V tokens,
+    q in, o out, one handle + one table entry per page."""
+    e = spec.elem_bytes
+    pages = (int(ctx) + spec.page_tokens - 1) // spec.page_tokens
+    return (int(ctx) * 2 * spec.n_kv_heads * spec.head_dim * e + spec.n_q_heads * spec.head_dim * e
+            + spec.n_q_heads * spec.head_dim * 4 + pages * 8)
+
+
+def ssm_bytes(spec):
+    """Algorithmic bytes of one SSM layer for one request: state read + write,
+    x in, y out, B, C, dt and the handle + table entry."""
+    e = spec.elem_bytes
+    H, P, N = spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate
+    return 2 * H * P * N * 4 + H * P * e + H * P * 4 + 2 * N * e + H * 4 + 8
+
+
+def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=16):
+    """Times the CPU oracle, as it stands, on the first requests of the batch
+    (all 32 layers each) until about budget_s seconds of work are done."""
+    import numpy as np
+    from oracle import avmp_oracle as orc
+    from paper_2605_22416_amd import inputs
+    shape = orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
+                      spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate)
+    done, elapsed, nbytes = [], 0.0, 0
+    ref_o, ref_y = {}, {}
+    for r in range(min(max_requests, sc.batch)):
+        n_pages = int(sc.n_pages[r])
+        arena = (n_pages * spec.n_attn + 2) * spec.kv_page_bytes + (spec.n_ssm + 1) * spec.ssm_block_bytes
+        op = orc.Pools(shape, arena, n_pages * spec.n_attn + 2, spec.n_ssm + 1)
+        kv = np.full((spec.n_attn, 1, n_pages), 0xFFFFFFFF, dtype=np.uint32)
+        for la in range(spec.n_attn):
+            kv[la, 0] = op.alloc(orc.POOL_KV, n_pages)[1]
+        ssm = np.asarray(op.alloc(orc.POOL_SSM, spec.n_ssm)[1], dtype=np.uint32).reshape(spec.n_ssm, 1)
+        for la in range(spec.n_attn):
+            for i in range(n_pages):
+                op.unit_view(int(kv[la, 0, i]))[:] = inputs.unit_content(spec, seed, 0, la, r, i)
+        for ls in range(spec.n_ssm):
+            op.unit_view(int(ssm[ls, 0]))[:] = inputs.unit_content(spec, seed, 1, ls, r, 0)
+        one = {k: (v if k == "A" else v[:, r: r + 1]) for k, v in inp.items()}
+        t0 = time.perf_counter()
+        o, y = op.decode_step(spec.layer_kinds, kv, sc.ctx[r: r + 1], one["q"], ssm, one["x"],
+                              one["dt"], one["A"], one["B"], one["C"])
+        elapsed += time.perf_counter() - t0
+        nbytes += spec.n_attn * attention_bytes(spec, sc.ctx[r]) + spec.n_ssm * ssm_bytes(spec)
+        ref_o[r], ref_y[r] = o[:, 0], y[:, 0]
+        done.append(r)
+        if elapsed >= budget_s and len(done) >= 2:
+            break
+    return {"value": nbytes / elapsed / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "requests 0..%d of the batch (all %d layers each), %.1f s of oracle time, "
+                      "same algorithmic-byte numerator" % (done[-1], len(spec.layer_kinds), elapsed),
+            "us_per_step_extrapolated": elapsed / len(done) * sc.batch * 1e6}, ref_o, ref_y
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--seed", type=int, default=1002)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernels with HIP events in the timed region")
+    ap.add_argument("--fill-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on ONE GPU (pools, table and kernels are device-local; "
+              "no collectives exist to measure); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_22416_amd import binding as av
+    from paper_2605_22416_amd import inputs
+    from paper_2605_22416_amd.session import DeviceSession
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    spec = inputs.JAMBA_MINI
+    sc = inputs.make_scenario(spec, "uniform_short", args.batch, args.seed)
+    inp = inputs.step_inputs(spec, sc.batch, args.seed)
+    t0 = time.perf_counter()
+    ses = DeviceSession(sc, fill_byte=None)
+    ses.fill(threads=args.fill_threads)
+    setup_s = time.perf_counter() - t0
+    stream = torch.cuda.current_stream()
+    st, keep, o, y = ses.prepare_step(inp)
+
+    # ---- correctness of the very first step against the oracle sample ----------------
+    base, parity = None, None
+    ses.launch(st, stream)
+    torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        base, ref_o, ref_y = cpu_baseline(spec, sc, inp, args.seed)
+        o_h, y_h = o.cpu().numpy(), y.cpu().numpy()
+        eo = ey = 0.0
+        for r in ref_o:
+            eo = max(eo, float((np.abs(o_h[:, r] - ref_o[r]).max(axis=-1)
+                                / np.maximum(np.abs(ref_o[r]).max(axis=-1), 1e-30)).max()))
+            ey = max(ey, float((np.abs(y_h[:, r] - ref_y[r]).max(axis=-1)
+                                / np.maximum(np.abs(ref_y[r]).max(axis=-1), 1e-30)).max()))
+        parity = {"requests": len(ref_o), "attention_max_rel_err": eo, "ssm_max_rel_err": ey,
+                  "tolerance": 2e-3}
+        if eo > 2e-3 or ey > 2e-3:
+            print("bench.py: GPU step disagrees with the oracle: %r" % parity, file=sys.stderr)
+            sys.exit(1)
+
+    # ---- the timed step ----------------------------------------------------------------
+    ghost_pages = int(round(float(sc.n_pages.mean())))
+    rc, ghost_kv = av.avmp_alloc(ses.p, 0, ghost_pages * spec.n_attn)
+    assert rc == av.AVMP_OK, av.avmp_last_error()
+    rc, ghost_ssm = av.avmp_alloc(ses.p, 1, spec.n_ssm)
+    assert rc == av.AVMP_OK, av.avmp_last_error()
+    mig_pages = 128
+    mig_blocks_back = mig_pages * spec.kv_page_bytes // spec.ssm_block_bytes
+    copies = [0]
+
+    def one_step():
+        nonlocal ghost_kv, ghost_ssm
+        assert av.avmp_free(ses.p, np.concatenate([ghost_kv, ghost_ssm])) == av.AVMP_OK
+        rc1, ghost_kv = av.avmp_alloc(ses.p, 0, ghost_pages * spec.n_attn)
+        rc2, ghost_ssm = av.avmp_alloc(ses.p, 1, spec.n_ssm)
+        assert rc1 == av.AVMP_OK and rc2 == av.AVMP_OK
+        ses.launch(st, stream)
+        rc1, res = av.avmp_migrate(ses.p, 0, mig_pages, stream)
+        assert rc1 == av.AVMP_OK, av.avmp_last_error()
+        copies[0] += res.units_copied
+        rc2, res = av.avmp_migrate(ses.p, 1, mig_blocks_back, stream)
+        assert rc2 == av.AVMP_OK, av.avmp_last_error()
+        copies[0] += res.units_copied * (spec.ssm_block_bytes // spec.kv_page_bytes)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = not args.no_kernel_events
+    av.avmp_profile_enable(ses.p, events)
+    av.avmp_profile_read(ses.p, stream)
+    copies[0] = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    rc, prof = av.avmp_profile_read(ses.p, stream)
+    av.avmp_profile_enable(ses.p, False)
+    rc, faults = av.avmp_device_faults(ses.p)
+    assert rc == av.AVMP_OK and faults == 0, "untranslatable handles: %d" % faults
+    assert np.isfinite(o.cpu().numpy()).all() and np.isfinite(y.cpu().numpy()).all()
+
+    attn_layer_bytes = sum(attention_bytes(spec, c) for c in sc.ctx)
+    ssm_layer_bytes = sc.batch * ssm_bytes(spec)
+    copy_bytes_step = copies[0] / args.steps * 2 * spec.kv_page_bytes
+    step_bytes = spec.n_attn * attn_layer_bytes + spec.n_ssm * ssm_layer_bytes + copy_bytes_step
+    ms_per_step = wall / args.steps * 1e3
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    kernels = {}
+    per_launch = {"attention": attn_layer_bytes, "ssm": ssm_layer_bytes}
+    for name, (ms, n) in prof.items():
+        if n:
+            k = {"launches": int(n), "avg_us": ms / n * 1e3}
+            if name in per_launch:
+                k["GBps"] = per_launch[name] / (ms / n * 1e-3) / 1e9
+            kernels[name] = k
+    roofline = None
+    if "ssm" in kernels:
+        a = kernels["ssm"]["GBps"]
+        roofline = {"kernel": "ssm_update_kernel", "bound": "hbm", "achieved": a,
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
+                    "traffic": None, "bytes_per_launch": ssm_layer_bytes,
+                    "avg_launch_us": kernels["ssm"]["avg_us"]}
+
+    # ---- migration sweep (outside the timed region): pages/s of capacity moved ----------
+    sweep = []
+    free_kv = av.avmp_stats(ses.p)["free"][0]
+    av.avmp_profile_enable(ses.p, True)
+    for n in (64, 1024, 3072):
+        if n > free_kv:
+            continue
+        back = n * spec.kv_page_bytes // spec.ssm_block_bytes
+        av.avmp_profile_read(ses.p, stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        rc, res = av.avmp_migrate(ses.p, 0, n, stream)
+        assert rc == av.AVMP_OK
+        torch.cuda.synchronize()
+        dt_wall = time.perf_counter() - t1
+        rc, pr = av.avmp_profile_read(ses.p, stream)
+        kms = pr["migrate_copy"][0]
+        rc2, _ = av.avmp_migrate(ses.p, 1, back, stream)
+        assert rc2 == av.AVMP_OK
+        sweep.append({"pages": n, "copied": int(res.units_copied),
+                      "pages_per_s_wall": n / dt_wall,
+                      "copy_GBps_kernel": (res.units_copied * 2 * spec.kv_page_bytes / (kms * 1e-3) / 1e9)
+                      if kms > 0 else None})
+    av.avmp_profile_enable(ses.p, False)
+    torch.cuda.synchronize()
+    ses.close()
+
+    out = {
+        "metric": "hybrid_decode_step_achieved_hbm_GBps_batch64",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "us_per_step": ms_per_step * 1e3,
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "jamba_mini_like decode step, uniform_short contexts U[128,2048], "
+                               "batch %d, 4 attention + 28 SSM layers, pools 1.2x demand, seeded "
+                               "random placement; step = churn + decode + 128-page migration "
+                               "round trip" % sc.batch,
+                   "batch": sc.batch, "seed": args.seed, "kernel_events_in_timed_region": events},
+        "algorithmic_bytes_per_step": step_bytes,
+        "migrated_pages_per_s": 2 * mig_pages * args.steps / wall,
+        "kernels": kernels, "migration_sweep": sweep, "setup_s": setup_s,
+        "roofline": roofline, "cpu_baseline": base, "parity_sample": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

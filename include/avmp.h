@@ -200,6 +200,25 @@ int avmp_stats(const avmp_pools_t* pools, avmp_stats_t* out);
  * kernels could not translate (such pages/blocks are skipped, never touched). */
 int avmp_device_faults(avmp_pools_t* pools, void* stream, uint64_t* out);
 
+/* Per-kernel timing with HIP events on the launch stream.  While enabled, every
+ * kernel the library launches is bracketed by an event pair; avmp_profile_read
+ * synchronises `stream`, adds up elapsed milliseconds and launch counts per
+ * kernel kind since the last read, writes them to *out and resets them. */
+enum {
+  AVMP_K_ATTENTION = 0,        /* paged GQA decode attention (per layer) */
+  AVMP_K_ATTENTION_MERGE = 1,  /* merge of per-chunk partial results (per layer) */
+  AVMP_K_SSM = 2,              /* SSM state update (per layer) */
+  AVMP_K_MIGRATE_COPY = 3,     /* migration copy + remap */
+  AVMP_K_TABLE = 4,            /* table scatter + zero fill of new SSM blocks */
+  AVMP_K_COUNT = 5
+};
+typedef struct avmp_profile {
+  double ms[AVMP_K_COUNT];
+  uint64_t launches[AVMP_K_COUNT];
+} avmp_profile_t;
+int avmp_profile_enable(avmp_pools_t* pools, int on);
+int avmp_profile_read(avmp_pools_t* pools, void* stream, avmp_profile_t* out);
+
 /* Text of the last error raised on the calling thread ("" if none). */
 const char* avmp_last_error(void);
 

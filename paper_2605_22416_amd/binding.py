@@ -91,6 +91,15 @@ class avmp_step_t(C.Structure):
                 ("C", C.c_void_p), ("y", C.c_void_p)]
 
 
+AVMP_K_ATTENTION, AVMP_K_ATTENTION_MERGE, AVMP_K_SSM, AVMP_K_MIGRATE_COPY, AVMP_K_TABLE = range(5)
+AVMP_K_COUNT = 5
+KERNEL_NAMES = ("attention", "attention_merge", "ssm", "migrate_copy", "table")
+
+
+class avmp_profile_t(C.Structure):
+    _fields_ = [("ms", C.c_double * AVMP_K_COUNT), ("launches", C.c_uint64 * AVMP_K_COUNT)]
+
+
 _P = C.c_void_p
 lib.avmp_last_error.restype = C.c_char_p
 lib.avmp_last_error.argtypes = []
@@ -107,9 +116,11 @@ lib.avmp_resolve.argtypes = [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.
                              C.POINTER(C.c_uint64)]
 lib.avmp_stats.argtypes = [_P, C.POINTER(avmp_stats_t)]
 lib.avmp_device_faults.argtypes = [_P, _P, C.POINTER(C.c_uint64)]
+lib.avmp_profile_enable.argtypes = [_P, C.c_int]
+lib.avmp_profile_read.argtypes = [_P, _P, C.POINTER(avmp_profile_t)]
 for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_alloc", "avmp_free",
            "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
-           "avmp_stats", "avmp_device_faults"):
+           "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read"):
     getattr(lib, _f).restype = C.c_int
 
 
@@ -237,3 +248,14 @@ def avmp_device_faults(pools, stream=None):
     out = C.c_uint64()
     rc = lib.avmp_device_faults(pools, _stream(stream), C.byref(out))
     return rc, out.value
+
+
+def avmp_profile_enable(pools, on: bool) -> int:
+    return lib.avmp_profile_enable(pools, 1 if on else 0)
+
+
+def avmp_profile_read(pools, stream=None):
+    """Returns (rc, {kernel name: (total ms, launches)})."""
+    out = avmp_profile_t()
+    rc = lib.avmp_profile_read(pools, _stream(stream), C.byref(out))
+    return rc, {KERNEL_NAMES[k]: (out.ms[k], out.launches[k]) for k in range(AVMP_K_COUNT)}

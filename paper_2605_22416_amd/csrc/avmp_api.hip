@@ -95,6 +95,30 @@ struct avmp_pools {
   std::vector<uint32_t> pending_zero;  // SSM slots to clear
   Staging staging;
 
+  // per-kernel timing: event pairs on the launch stream, summed at read time
+  struct ProfRec {
+    int kind;
+    hipEvent_t a, b;
+  };
+  bool profiling = false;
+  std::vector<ProfRec> prof;       // records in use since the last read
+  std::vector<ProfRec> prof_free;  // event pairs ready for reuse
+
+  int prof_start(int kind, hipStream_t s) {
+    ProfRec r{};
+    if (!prof_free.empty()) {
+      r = prof_free.back();
+      prof_free.pop_back();
+    } else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) {
+      return -1;
+    }
+    r.kind = kind;
+    (void)hipEventRecord(r.a, s);
+    prof.push_back(r);
+    return int(prof.size()) - 1;
+  }
+  void prof_stop(int idx, hipStream_t s) { (void)hipEventRecord(prof[size_t(idx)].b, s); }
+
   avmp::DevPools dev_view() const {
     avmp::DevPools P{};
     P.arena = arena;
@@ -135,6 +159,18 @@ bool shape_from_config(const avmp_config_t* c, avmp::ShapeArgs* s) {
   return true;
 }
 
+struct ProfScope {
+  avmp_pools* p;
+  hipStream_t s;
+  int idx = -1;
+  ProfScope(avmp_pools* pools, int kind, hipStream_t stream) : p(pools), s(stream) {
+    if (p->profiling) idx = p->prof_start(kind, s);
+  }
+  ~ProfScope() {
+    if (idx >= 0) p->prof_stop(idx, s);
+  }
+};
+
 // Queue -> device: table entries (coalesced to the last value per index, so the
 // scatter has no ordering hazard) and zero fills of freshly allocated SSM blocks.
 int flush_pending(avmp_pools* p, hipStream_t s) {
@@ -155,11 +191,15 @@ int flush_pending(avmp_pools* p, hipStream_t s) {
   char* host = static_cast<char*>(b->host);
   if (upd_bytes) std::memcpy(host, upd.data(), upd_bytes);
   if (zero_bytes) std::memcpy(host + upd_bytes, p->pending_zero.data(), zero_bytes);
-  HIP_TRY(avmp::launch_table_updates(p->table_dev, reinterpret_cast<const avmp::TableUpdate*>(host),
-                                     uint32_t(upd.size()), s));
-  HIP_TRY(avmp::launch_zero_units(p->dev_view(), AVMP_POOL_SSM,
-                                  reinterpret_cast<const uint32_t*>(host + upd_bytes),
-                                  uint32_t(p->pending_zero.size()), s));
+  {
+    ProfScope scope(p, AVMP_K_TABLE, s);
+    HIP_TRY(avmp::launch_table_updates(p->table_dev,
+                                       reinterpret_cast<const avmp::TableUpdate*>(host),
+                                       uint32_t(upd.size()), s));
+    HIP_TRY(avmp::launch_zero_units(p->dev_view(), AVMP_POOL_SSM,
+                                    reinterpret_cast<const uint32_t*>(host + upd_bytes),
+                                    uint32_t(p->pending_zero.size()), s));
+  }
   HIP_TRY(p->staging.release_after(b, s));
   p->pending.clear();
   p->pending_zero.clear();
@@ -241,6 +281,11 @@ int avmp_pools_destroy(avmp_pools_t* p) {
   if (p->has_device) {
     (void)hipDeviceSynchronize();
     p->staging.destroy();
+    for (auto* v : {&p->prof, &p->prof_free})
+      for (auto& r : *v) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+      }
     if (p->ws) (void)hipFree(p->ws);
     (void)hipFree(p->table_dev);
     (void)hipFree(p->faults_dev);
@@ -303,9 +348,12 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
     HIP_TRY(p->staging.acquire(bytes, &b));
     std::memcpy(b->host, moves.data(), bytes);
     // capacities in the view are already the new ones; the copy needs none of them
-    HIP_TRY(avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor,
-                                      static_cast<const avmp::Move*>(b->host),
-                                      uint32_t(moves.size()), s));
+    {
+      ProfScope scope(p, AVMP_K_MIGRATE_COPY, s);
+      HIP_TRY(avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor,
+                                        static_cast<const avmp::Move*>(b->host),
+                                        uint32_t(moves.size()), s));
+    }
     HIP_TRY(p->staging.release_after(b, s));
   }
   if (out) {
@@ -367,7 +415,14 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.n_kv_heads = c.n_kv_heads;
       a.head_dim = c.head_dim;
       a.dtype = c.dtype;
-      HIP_TRY(avmp::launch_attention(a, s));
+      {
+        ProfScope scope(p, AVMP_K_ATTENTION, s);
+        HIP_TRY(avmp::launch_attention(a, s));
+      }
+      {
+        ProfScope scope(p, AVMP_K_ATTENTION_MERGE, s);
+        HIP_TRY(avmp::launch_attention_merge(a, s));
+      }
       ++ia;
     } else {
       avmp::SsmLaunch a{};
@@ -385,7 +440,10 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.headdim = c.ssm_headdim;
       a.dstate = c.ssm_dstate;
       a.dtype = c.dtype;
-      HIP_TRY(avmp::launch_ssm(a, s));
+      {
+        ProfScope scope(p, AVMP_K_SSM, s);
+        HIP_TRY(avmp::launch_ssm(a, s));
+      }
       ++is;
     }
   }
@@ -430,6 +488,29 @@ int avmp_stats(const avmp_pools_t* p, avmp_stats_t* out) {
   out->units_copied = c.units_copied;
   out->bytes_migrated = c.bytes_migrated;
   out->bytes_wasted = c.bytes_wasted;
+  return AVMP_OK;
+}
+
+int avmp_profile_enable(avmp_pools_t* p, int on) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  p->profiling = on != 0;
+  return AVMP_OK;
+}
+
+int avmp_profile_read(avmp_pools_t* p, void* stream, avmp_profile_t* out) {
+  if (p == nullptr || out == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  std::memset(out, 0, sizeof(*out));
+  for (const auto& r : p->prof) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    out->ms[r.kind] += double(ms);
+    out->launches[r.kind] += 1;
+    p->prof_free.push_back(r);
+  }
+  p->prof.clear();
   return AVMP_OK;
 }
 

@@ -334,6 +334,11 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
     attn_generic_kernel<float><<<grid, dim3(64), 0, s>>>(a);
   else
     attn_generic_kernel<uint16_t><<<grid, dim3(64), 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s) {
+  if (a.batch == 0) return hipSuccess;
   attn_merge_kernel<<<dim3(a.n_q_heads, a.batch), dim3(64), 0, s>>>(a);
   return hipGetLastError();
 }

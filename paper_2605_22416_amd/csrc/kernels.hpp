@@ -37,6 +37,7 @@ struct SsmLaunch {
 };
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
+hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s);
 hipError_t launch_table_updates(uint32_t* table, const TableUpdate* upd, uint32_t n, hipStream_t s);
 hipError_t launch_zero_units(const DevPools& P, int pool, const uint32_t* slots, uint32_t n,
