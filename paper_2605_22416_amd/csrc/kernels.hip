@@ -329,6 +329,7 @@ hipError_t launch_translate(const DevPools& P, const uint32_t* handles, uint32_t
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
+  if (attention_mfma_supported(a)) return launch_attention_mfma(a, s);
   const dim3 grid(a.n_q_heads, a.max_chunks, a.batch);
   if (a.dtype == 0)
     attn_generic_kernel<float><<<grid, dim3(64), 0, s>>>(a);

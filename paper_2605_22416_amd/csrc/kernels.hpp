@@ -37,6 +37,9 @@ struct SsmLaunch {
 };
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
+// matrix-core variant (attn_mfma.hip): bf16, head_dim 64/128/256, query group <= 16
+bool attention_mfma_supported(const AttnLaunch& a);
+hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s);
 hipError_t launch_table_updates(uint32_t* table, const TableUpdate* upd, uint32_t n, hipStream_t s);
