@@ -191,29 +191,58 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnLaunch a) {
   }
   if (nch == 1) return;            // written directly by the attention kernel
   const size_t base = (size_t(r) * a.max_chunks) * Hq + j;
-  float M = -INFINITY;
-  for (uint32_t c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[(base + size_t(c) * Hq) * 2]);
-  float L = 0.f;
-  for (uint32_t c = 0; c < nch; ++c) {
-    const size_t idx = base + size_t(c) * Hq;
-    L += a.part_ml[idx * 2 + 1] * exp2f(a.part_ml[idx * 2] - M);
+  // lane c holds chunk c's statistics (nch <= 64); the weights are broadcast
+  // while the partial outputs are summed in chunk order
+  float mc = -INFINITY, lc = 0.f;
+  if (lane < nch) {
+    mc = a.part_ml[(base + size_t(lane) * Hq) * 2];
+    lc = a.part_ml[(base + size_t(lane) * Hq) * 2 + 1];
   }
-  for (uint32_t d = lane; d < D; d += 64) {
+  float M = mc;
+  for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  const float w = lane < nch ? exp2f(mc - M) : 0.f;
+  float L = lc * w;
+  for (int o = 32; o; o >>= 1) L += __shfl_xor(L, o);
+  for (uint32_t d0 = 0; d0 < D; d0 += 64) {
+    const uint32_t d = d0 + lane;
     float sum = 0.f;
-    for (uint32_t c = 0; c < nch; ++c) {
-      const size_t idx = base + size_t(c) * Hq;
-      sum += a.part_o[idx * D + d] * exp2f(a.part_ml[idx * 2] - M);
+    uint32_t c = 0;
+    for (; c + 4 <= nch; c += 4) {
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        v[u] = d < D ? a.part_o[(base + size_t(c + u) * Hq) * D + d] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sum += v[u] * __shfl(w, int(c + u));
     }
-    orow[d] = L > 0.f ? sum / L : 0.f;
+    for (; c < nch; ++c) {
+      const float v = d < D ? a.part_o[(base + size_t(c) * Hq) * D + d] : 0.f;
+      sum += v * __shfl(w, int(c));
+    }
+    if (d < D) orow[d] = L > 0.f ? sum / L : 0.f;
   }
 }
 
 // ---------------------------------------------------------------------------
 // SSM single-token state update, in place.  One workgroup per (head, request):
-// the head's [P][N] fp32 tile is streamed once in and once out with 16-byte
-// accesses; a row's N values sit in N/4 adjacent lanes, which also reduce
-// y = sum_n S*C.  ROWS independent 16-byte loads are in flight per lane.
+// the head's [P][N] fp32 tile (32 KiB at 64 x 128) is streamed once in and once
+// out with 16-byte accesses; a row's N values sit in N/4 adjacent lanes, which
+// also reduce y = sum_n S*C.  The state is touched exactly once per step, so
+// its loads and stores carry the non-temporal hint.  1024-thread workgroups
+// move a whole tile in one burst of loads followed by one burst of stores;
+// on MI355X that measured 6.3 TB/s against 5.2 TB/s for 256-thread groups.
 // ---------------------------------------------------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 load_stream(const float* p) {
+  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(float* p, float4 v) {
+  const f32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(p));
+}
+
 template <typename E>
 __device__ __forceinline__ float4 load4(const E* p);
 template <>
@@ -227,21 +256,21 @@ __device__ __forceinline__ float4 load4<uint16_t>(const uint16_t* p) {
                      __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
 }
 
-template <typename E, int ROWS>
-__global__ __launch_bounds__(256) void ssm_update_kernel(SsmLaunch a) {
+template <typename E, int THREADS, int ROWS>
+__global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
   const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
   const uint32_t H = a.heads, Pd = a.headdim, N = a.dstate;
   const uint64_t off = translate_offset(a.P, a.handles[r], 1);
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
   if (off == ~0ull) {
     if (tid == 0) count_fault(a.P);
-    for (uint32_t p = tid; p < Pd; p += 256) yrow[p] = 0.f;
+    for (uint32_t p = tid; p < Pd; p += THREADS) yrow[p] = 0.f;
     return;
   }
   const uint32_t lpr = N / 4;                  // lanes per row (power of two, <= 64)
   const uint32_t col = tid & (lpr - 1);
   const uint32_t row0 = tid / lpr;
-  const uint32_t rpi = 256 / lpr;              // rows per pass of the workgroup
+  const uint32_t rpi = THREADS / lpr;          // rows per pass of the workgroup
   const float dt = a.dt[size_t(r) * H + h];
   const float decay = expf(dt * a.A[h]);
   const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
@@ -254,11 +283,15 @@ __global__ __launch_bounds__(256) void ssm_update_kernel(SsmLaunch a) {
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
       const uint32_t p = pbase + k * rpi;
-      if (p < Pd) s[k] = *reinterpret_cast<const float4*>(S + size_t(p) * N);
+      if (p < Pd) s[k] = load_stream(S + size_t(p) * N);
     }
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
       const uint32_t p = pbase + k * rpi;
+      // p < Pd is uniform over the lanes of a row and rows never straddle a
+      // wavefront, but the shuffles below run on all lanes and only the
+      // memory accesses are masked
+      float part = 0.f;
       if (p < Pd) {
         const float dtx = dt * load_elem<E>(xrow + p);
         float4 v = s[k];
@@ -266,17 +299,9 @@ __global__ __launch_bounds__(256) void ssm_update_kernel(SsmLaunch a) {
         v.y = decay * v.y + dtx * Bv.y;
         v.z = decay * v.z + dtx * Bv.z;
         v.w = decay * v.w + dtx * Bv.w;
-        *reinterpret_cast<float4*>(S + size_t(p) * N) = v;
-        s[k] = v;
+        store_stream(S + size_t(p) * N, v);
+        part = v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w;
       }
-    }
-#pragma unroll
-    for (int k = 0; k < ROWS; ++k) {
-      const uint32_t p = pbase + k * rpi;
-      // p < Pd is uniform over the lpr lanes of a row, and rows never straddle
-      // a 64-lane wavefront, but shuffle on all lanes anyway and mask the store
-      float part = 0.f;
-      if (p < Pd) part = s[k].x * Cv.x + s[k].y * Cv.y + s[k].z * Cv.z + s[k].w * Cv.w;
       for (uint32_t o = lpr >> 1; o; o >>= 1) part += __shfl_xor(part, int(o));
       if (p < Pd && col == 0) yrow[p] = part;
     }
@@ -347,10 +372,15 @@ hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s) {
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
   const dim3 grid(a.heads, a.batch);
-  if (a.dtype == 0)
-    ssm_update_kernel<float, 8><<<grid, dim3(256), 0, s>>>(a);
-  else
-    ssm_update_kernel<uint16_t, 8><<<grid, dim3(256), 0, s>>>(a);
+  // a head's tile is headdim x dstate/4 16-byte accesses: big tiles get 1024 threads
+  const bool big = uint64_t(a.headdim) * (a.dstate / 4) >= 1024;
+  if (a.dtype == 0) {
+    if (big) ssm_update_kernel<float, 1024, 2><<<grid, dim3(1024), 0, s>>>(a);
+    else ssm_update_kernel<float, 256, 4><<<grid, dim3(256), 0, s>>>(a);
+  } else {
+    if (big) ssm_update_kernel<uint16_t, 1024, 2><<<grid, dim3(1024), 0, s>>>(a);
+    else ssm_update_kernel<uint16_t, 256, 4><<<grid, dim3(256), 0, s>>>(a);
+  }
   return hipGetLastError();
 }
 
