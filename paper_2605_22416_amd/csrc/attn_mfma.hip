@@ -1,6 +1,17 @@
 // Paged GQA decode attention on the CDNA4 matrix cores (bf16 in, fp32
-// accumulate).  One wavefront per (KV head, chunk, request) serves the whole
-// query group of that KV head, so K and V are read from HBM exactly once.
+// accumulate).  A wavefront serves the whole query group of one KV head, so K
+// and V are read from HBM exactly once.
+//
+// Work split.  For each KV head the (request, page) pairs of the batch, in
+// logical order, form one sequence of `total` pages; it is cut into equal runs
+// of `ipw` pages and wavefront w walks run w, crossing request boundaries as it
+// goes.  A run that covers a whole request writes the output row; otherwise it
+// leaves a partial result (un-normalised sum, running max, running sum) that the
+// merge kernel combines in logical order.  Every wavefront moves the same
+// number of bytes, so the launch has no tail, and the split is a function of
+// the context lengths alone: physical placement and migration cannot change
+// one bit of the result.  A one-block plan kernel computes the page prefix sums
+// and each run's starting (request, page) once per decode step.
 //
 // The in-page layout is the matrix-core operand order, so operands go from
 // global memory to registers to MFMA with no LDS staging and no conversion:
@@ -24,12 +35,6 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ uint32_t resident_tokens_m(const AttnLaunch& a, uint32_t r) {
-  const uint32_t n = a.ctx[r];
-  const uint64_t room = uint64_t(a.max_pages) * 16u;
-  return n > room ? uint32_t(room) : n;
-}
-
 __device__ __forceinline__ uint64_t readlane64(uint64_t v, uint32_t lane) {
   const uint32_t lo = __builtin_amdgcn_readlane(uint32_t(v), lane);
   const uint32_t hi = __builtin_amdgcn_readlane(uint32_t(v >> 32), lane);
@@ -42,176 +47,319 @@ struct PageRegs {
   uint2 v[D / 16];     // V operand tiles
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// K and V are read once per step: non-temporal loads keep them from displacing
+// lines that will be reused (measured +12 % on the page walk).
+__device__ __forceinline__ uint4 load16_stream(const uint8_t* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 load8_stream(const uint8_t* p) {
+  const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+  return make_uint2(v.x, v.y);
+}
+
 template <int D>
 __device__ __forceinline__ void load_page(PageRegs<D>& pr, const uint8_t* kslab, const uint8_t* vslab,
                                           uint32_t lane) {
 #pragma unroll
-  for (int kk = 0; kk < D / 32; ++kk)
-    pr.k[kk] = *reinterpret_cast<const uint4*>(kslab + kk * 1024 + lane * 16);
+  for (int kk = 0; kk < D / 32; ++kk) pr.k[kk] = load16_stream(kslab + kk * 1024 + lane * 16);
   const uint32_t voff = (lane & 15) * 32 + (lane >> 4) * 8;
 #pragma unroll
-  for (int nt = 0; nt < D / 16; ++nt)
-    pr.v[nt] = *reinterpret_cast<const uint2*>(vslab + nt * 512 + voff);
+  for (int nt = 0; nt < D / 16; ++nt) pr.v[nt] = load8_stream(vslab + nt * 512 + voff);
+}
+
+__device__ __forceinline__ uint32_t pages_of(uint32_t ctx, uint32_t max_pages) {
+  const uint32_t n = (ctx >> 4) + ((ctx & 15u) ? 1u : 0u);
+  return n > max_pages ? max_pages : n;      // a context beyond the handle row is clamped
+}
+
+// One block: page prefix sums over the batch, run length, and each run's start.
+// plan[0] = total pages, plan[1] = pages per run (ipw).
+__global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restrict__ ctx, uint32_t batch,
+                                                         uint32_t max_pages, uint32_t runs,
+                                                         uint32_t* __restrict__ plan,
+                                                         uint32_t* __restrict__ prefix,
+                                                         uint2* __restrict__ desc) {
+  __shared__ uint32_t sums[1024];
+  const uint32_t tid = threadIdx.x;
+  const uint32_t seg = (batch + 1023) / 1024;
+  const uint32_t lo = min(batch, tid * seg), hi = min(batch, lo + seg);
+  uint32_t local = 0;
+  for (uint32_t r = lo; r < hi; ++r) local += pages_of(ctx[r], max_pages);
+  sums[tid] = local;
+  __syncthreads();
+  for (uint32_t off = 1; off < 1024; off <<= 1) {          // inclusive scan
+    const uint32_t add = tid >= off ? sums[tid - off] : 0;
+    __syncthreads();
+    sums[tid] += add;
+    __syncthreads();
+  }
+  uint32_t run = sums[tid] - local;                         // exclusive start of this segment
+  for (uint32_t r = lo; r < hi; ++r) {
+    prefix[r] = run;
+    run += pages_of(ctx[r], max_pages);
+  }
+  const uint32_t total = sums[1023];
+  const uint32_t ipw = total == 0 ? 1 : (total + runs - 1) / runs;
+  if (tid == 0) {
+    prefix[batch] = total;
+    plan[0] = total;
+    plan[1] = ipw;
+  }
+  __syncthreads();                                          // prefix[] visible to the block
+  for (uint32_t w = tid; w < runs; w += 1024) {
+    const uint64_t item = uint64_t(w) * ipw;
+    if (item >= total) {
+      desc[w] = make_uint2(batch, 0);
+      continue;
+    }
+    // last r with prefix[r] <= item; requests without pages share their prefix with
+    // the next one, so taking the LAST such r skips them
+    uint32_t a = 0, b = batch;                              // invariant: prefix[a] <= item < prefix[b]
+    while (b - a > 1) {
+      const uint32_t mid = (a + b) / 2;
+      if (prefix[mid] <= item) a = mid; else b = mid;
+    }
+    desc[w] = make_uint2(a, uint32_t(item) - prefix[a]);
+  }
 }
 
 template <int D>
 __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
   constexpr int KK = D / 32;
   constexpr int NT = D / 16;
-  const uint32_t g = blockIdx.x, c = blockIdx.y, r = blockIdx.z;
+  const uint32_t g = blockIdx.x, w = blockIdx.y;
   const uint32_t lane = threadIdx.x, n = lane & 15, jg = lane >> 4;
-  const uint32_t n_tok = resident_tokens_m(a, r);
-  const uint32_t n_pages = (n_tok + 15) / 16;
-  const uint32_t nch = chunk_count_for(n_pages);
-  if (c >= nch) return;
-  const uint32_t cp = chunk_pages_for(n_pages);
-  const uint32_t p0 = c * cp;
-  const uint32_t p1 = min(n_pages, p0 + cp);
+  const uint32_t total = a.plan[0], ipw = a.plan[1];
+  uint64_t item = uint64_t(w) * ipw;
+  if (item >= total) return;
+  const uint64_t item_end = min(uint64_t(total), item + ipw);
+  const uint2 start = a.desc[w];
+  uint32_t r = start.x, page = start.y;
   const uint32_t G = a.n_kv_heads, Hq = a.n_q_heads, Gq = Hq / G;
-
-  // Q^T operand: lane (n = head in group, jg) holds dims 32*kk + 8*jg .. +7
-  uint4 qreg[KK];
-  {
-    const uint16_t* qrow = static_cast<const uint16_t*>(a.q) + (size_t(r) * Hq + size_t(g) * Gq + n) * D;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qreg[kk] = n < Gq ? *reinterpret_cast<const uint4*>(qrow + 32 * kk + 8 * jg) : make_uint4(0, 0, 0, 0);
-  }
-
   const float scale_log2 = kLog2e / sqrtf(float(D));
-  float m = -INFINITY;        // running max of head n (log2 domain), same in all 4 lanes of the head
-  float lsum = 0.f;           // this lane's share of the running sum of head n
-  float4v acc[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) acc[nt] = float4v{0.f, 0.f, 0.f, 0.f};
-
   const size_t kslab_off = size_t(g) * D * 32;                        // bytes: [D/8][16][8] bf16
   const size_t vslab_off = size_t(G) * D * 32 + size_t(g) * D * 32;   // bytes: [D][16] bf16
 
-  auto process = [&](const PageRegs<D>& pr, uint32_t n_valid) {
-    float4v s = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pr.k[kk]),
-                                                  __builtin_bit_cast(bf16x8, qreg[kk]), s, 0, 0, 0);
-    // s[i] = q_head(n) . k_token(4*jg + i)
-    float sv[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) sv[i] = (4 * jg + i < n_valid) ? s[i] * scale_log2 : -INFINITY;
-    float pm = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-    pm = fmaxf(pm, __shfl_xor(pm, 16));
-    pm = fmaxf(pm, __shfl_xor(pm, 32));
-    const float m_new = fmaxf(m, pm);
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-    m = m_new;
-    float p[4];
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      p[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
-      hi[i] = __float_as_uint(p[i]) & 0xFFFF0000u;
-      lo[i] = __float_as_uint(p[i] - __uint_as_float(hi[i]));
+  while (item < item_end && r < a.batch) {
+    const uint32_t n_pages = pages_of(a.ctx[r], a.max_pages);
+    if (page >= n_pages) {             // request without pages (or exhausted): next one
+      ++r;
+      page = 0;
+      continue;
     }
-    lsum = lsum * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-    // two bf16 per register: low half = even token, high half = odd token
-    const uint2 ahi = make_uint2((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
-    const uint2 alo = make_uint2((lo[0] >> 16) | (lo[1] & 0xFFFF0000u), (lo[2] >> 16) | (lo[3] & 0xFFFF0000u));
-    const short4v a_hi = __builtin_bit_cast(short4v, ahi);
-    const short4v a_lo = __builtin_bit_cast(short4v, alo);
-    // accumulator row i of lane group jg belongs to head 4*jg + i, whose alpha sits in lane 4*jg + i
-    float al[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, int(4 * jg + i));
-    // tokens at or beyond n_valid hold arbitrary bits: clear them so 0 * x stays 0
-    uint32_t mx = 0xFFFFFFFFu, my = 0xFFFFFFFFu;
-    if (n_valid < 16) {
-      mx = (4 * jg + 0 < n_valid ? 0x0000FFFFu : 0u) | (4 * jg + 1 < n_valid ? 0xFFFF0000u : 0u);
-      my = (4 * jg + 2 < n_valid ? 0x0000FFFFu : 0u) | (4 * jg + 3 < n_valid ? 0xFFFF0000u : 0u);
-    }
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      float4v o = acc[nt];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) o[i] *= al[i];
-      const short4v vb = __builtin_bit_cast(short4v, make_uint2(pr.v[nt].x & mx, pr.v[nt].y & my));
-      o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, vb, o, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, vb, o, 0, 0, 0);
-      acc[nt] = o;
-    }
-  };
+    const uint32_t n_tok = min(a.ctx[r], n_pages * 16u);
+    const uint32_t p0 = page;
+    const uint32_t p1 = uint32_t(min(uint64_t(n_pages), uint64_t(page) + (item_end - item)));
 
-  // Pages are taken 64 at a time: each lane translates one handle, then the
-  // wavefront walks them with one page of loads in flight ahead of the math.
-  for (uint32_t base = p0; base < p1; base += 64) {
-    const uint32_t cnt = min(64u, p1 - base);
-    uint64_t my_off = ~0ull;
-    if (lane < cnt) {
-      my_off = translate_offset(a.P, a.handles[size_t(r) * a.max_pages + base + lane], 0);
-      if (my_off == ~0ull) count_fault(a.P);
+    // Q^T operand: lane (n = head in group, jg) holds dims 32*kk + 8*jg .. +7
+    uint4 qreg[KK];
+    {
+      const uint16_t* qrow =
+          static_cast<const uint16_t*>(a.q) + (size_t(r) * Hq + size_t(g) * Gq + n) * D;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        qreg[kk] = n < Gq ? *reinterpret_cast<const uint4*>(qrow + 32 * kk + 8 * jg)
+                          : make_uint4(0, 0, 0, 0);
     }
-    PageRegs<D> ra, rb;
-    uint64_t off_a = readlane64(my_off, 0);
-    if (off_a != ~0ull) load_page<D>(ra, a.P.arena + off_a + kslab_off, a.P.arena + off_a + vslab_off, lane);
-    for (uint32_t i = 0; i < cnt; i += 2) {
-      const uint64_t off_b = i + 1 < cnt ? readlane64(my_off, i + 1) : ~0ull;
-      if (off_b != ~0ull) load_page<D>(rb, a.P.arena + off_b + kslab_off, a.P.arena + off_b + vslab_off, lane);
-      if (off_a != ~0ull) process(ra, min(16u, n_tok - (base + i) * 16));
-      off_a = i + 2 < cnt ? readlane64(my_off, i + 2) : ~0ull;
-      if (off_a != ~0ull) load_page<D>(ra, a.P.arena + off_a + kslab_off, a.P.arena + off_a + vslab_off, lane);
-      if (off_b != ~0ull) process(rb, min(16u, n_tok - (base + i + 1) * 16));
+    float m = -INFINITY;   // running max of head n (log2 domain), same in the head's 4 lanes
+    float lsum = 0.f;      // this lane's share of the running sum of head n
+    float4v acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    auto process = [&](const PageRegs<D>& pr, uint32_t n_valid) {
+      float4v s = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pr.k[kk]),
+                                                    __builtin_bit_cast(bf16x8, qreg[kk]), s, 0, 0, 0);
+      // s[i] = q_head(n) . k_token(4*jg + i)
+      float sv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sv[i] = (4 * jg + i < n_valid) ? s[i] * scale_log2 : -INFINITY;
+      float pm = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+      pm = fmaxf(pm, __shfl_xor(pm, 16));
+      pm = fmaxf(pm, __shfl_xor(pm, 32));
+      const float m_new = fmaxf(m, pm);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      float p[4];
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(sv[i] - m_new);
+        hi[i] = __float_as_uint(p[i]) & 0xFFFF0000u;
+        lo[i] = __float_as_uint(p[i] - __uint_as_float(hi[i]));
+      }
+      lsum = lsum * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+      // two bf16 per register: low half = even token, high half = odd token
+      const uint2 ahi = make_uint2((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+      const uint2 alo = make_uint2((lo[0] >> 16) | (lo[1] & 0xFFFF0000u),
+                                   (lo[2] >> 16) | (lo[3] & 0xFFFF0000u));
+      const short4v a_hi = __builtin_bit_cast(short4v, ahi);
+      const short4v a_lo = __builtin_bit_cast(short4v, alo);
+      // accumulator row i of lane group jg is head 4*jg + i, whose alpha sits in lane 4*jg + i
+      float al[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, int(4 * jg + i));
+      // tokens at or beyond n_valid hold arbitrary bits: clear them so 0 * x stays 0
+      uint32_t mx = 0xFFFFFFFFu, my = 0xFFFFFFFFu;
+      if (n_valid < 16) {
+        mx = (4 * jg + 0 < n_valid ? 0x0000FFFFu : 0u) | (4 * jg + 1 < n_valid ? 0xFFFF0000u : 0u);
+        my = (4 * jg + 2 < n_valid ? 0x0000FFFFu : 0u) | (4 * jg + 3 < n_valid ? 0xFFFF0000u : 0u);
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float4v o = acc[nt];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] *= al[i];
+        const short4v vb =
+            __builtin_bit_cast(short4v, make_uint2(pr.v[nt].x & mx, pr.v[nt].y & my));
+        o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, vb, o, 0, 0, 0);
+        o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, vb, o, 0, 0, 0);
+        acc[nt] = o;
+      }
+    };
+
+    // Pages are taken 64 at a time: each lane translates one handle, then the
+    // wavefront walks them with one page of loads in flight ahead of the math.
+    for (uint32_t base = p0; base < p1; base += 64) {
+      const uint32_t cnt = min(64u, p1 - base);
+      uint64_t my_off = ~0ull;
+      if (lane < cnt) {
+        my_off = translate_offset(a.P, a.handles[size_t(r) * a.max_pages + base + lane], 0);
+        if (my_off == ~0ull) count_fault(a.P);
+      }
+      PageRegs<D> ra, rb;
+      uint64_t off_a = readlane64(my_off, 0);
+      if (off_a != ~0ull)
+        load_page<D>(ra, a.P.arena + off_a + kslab_off, a.P.arena + off_a + vslab_off, lane);
+      for (uint32_t i = 0; i < cnt; i += 2) {
+        const uint64_t off_b = i + 1 < cnt ? readlane64(my_off, i + 1) : ~0ull;
+        if (off_b != ~0ull)
+          load_page<D>(rb, a.P.arena + off_b + kslab_off, a.P.arena + off_b + vslab_off, lane);
+        if (off_a != ~0ull) process(ra, min(16u, n_tok - (base + i) * 16));
+        off_a = i + 2 < cnt ? readlane64(my_off, i + 2) : ~0ull;
+        if (off_a != ~0ull)
+          load_page<D>(ra, a.P.arena + off_a + kslab_off, a.P.arena + off_a + vslab_off, lane);
+        if (off_b != ~0ull) process(rb, min(16u, n_tok - (base + i + 1) * 16));
+      }
     }
+
+    // finish the row sums: head n's sum is spread over its 4 lanes
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    float lh[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lh[i] = __shfl(lsum, int(4 * jg + i));
+
+    if (p0 == 0 && p1 == n_pages) {          // the run covers the whole request: final row
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t head = 4 * jg + i;
+        if (head < Gq) {
+          float* orow = a.o + (size_t(r) * Hq + size_t(g) * Gq + head) * D;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) orow[16 * nt + n] = lh[i] > 0.f ? acc[nt][i] / lh[i] : 0.f;
+        }
+      }
+    } else {
+      // a run leaves at most two partial results: slot 1 for the piece that starts its
+      // request, slot 0 for the piece that continues one
+      const size_t slot = (size_t(g) * a.runs + w) * 2 + (p0 == 0 ? 1 : 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t head = 4 * jg + i;
+        if (head < Gq) {
+          const size_t idx = slot * Gq + head;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) a.part_o[idx * D + 16 * nt + n] = acc[nt][i];
+        }
+      }
+      if (jg == 0 && n < Gq) {
+        const size_t idx = slot * Gq + n;
+        a.part_ml[idx * 2] = m;
+        a.part_ml[idx * 2 + 1] = lsum;
+      }
+    }
+    item += p1 - p0;
+    page = 0;
+    ++r;
   }
+}
 
-  // finish the row sums: head n's sum is spread over its 4 lanes
-  lsum += __shfl_xor(lsum, 16);
-  lsum += __shfl_xor(lsum, 32);
-  float lh[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) lh[i] = __shfl(lsum, int(4 * jg + i));
-
-  if (nch == 1) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t head = 4 * jg + i;
-      if (head < Gq) {
-        float* orow = a.o + (size_t(r) * Hq + size_t(g) * Gq + head) * D;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) orow[16 * nt + n] = lh[i] > 0.f ? acc[nt][i] / lh[i] : 0.f;
-      }
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t head = 4 * jg + i;
-      if (head < Gq) {
-        const size_t idx = (size_t(r) * a.max_chunks + c) * Hq + size_t(g) * Gq + head;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) a.part_o[idx * D + 16 * nt + n] = acc[nt][i];
-      }
-    }
-    if (jg == 0 && n < Gq) {
-      const size_t idx = (size_t(r) * a.max_chunks + c) * Hq + size_t(g) * Gq + n;
-      a.part_ml[idx * 2] = m;
-      a.part_ml[idx * 2 + 1] = lsum;
-    }
+// Combines the partial results of one (query head, request) in logical (run) order.
+__global__ __launch_bounds__(64) void attn_merge_runs_kernel(AttnLaunch a) {
+  const uint32_t j = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+  const uint32_t D = a.head_dim, Hq = a.n_q_heads, Gq = Hq / a.n_kv_heads;
+  const uint32_t g = j / Gq, head = j % Gq;
+  float* orow = a.o + (size_t(r) * Hq + j) * D;
+  if (j == 0 && lane == 0 && uint64_t(a.ctx[r]) > uint64_t(a.max_pages) * 16u) count_fault(a.P);
+  const uint32_t start = a.prefix[r], end = a.prefix[r + 1];
+  if (start == end) {                       // no resident tokens: zero row
+    for (uint32_t d = lane; d < D; d += 64) orow[d] = 0.f;
+    return;
+  }
+  const uint32_t ipw = a.plan[1];
+  const uint32_t wa = start / ipw, wb = (end - 1) / ipw;
+  if (wa == wb) return;                     // one run covered it and wrote the row
+  const uint32_t np = wb - wa + 1;
+  auto piece = [&](uint32_t k) -> size_t {  // first piece starts the request (slot 1)
+    return ((size_t(g) * a.runs + wa + k) * 2 + (k == 0 ? 1 : 0)) * Gq + head;
+  };
+  float M = -INFINITY;
+  for (uint32_t k = lane; k < np; k += 64) M = fmaxf(M, a.part_ml[piece(k) * 2]);
+  for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  float L = 0.f;
+  for (uint32_t k = 0; k < np; ++k)         // sequential: a fixed order for any piece count
+    L += a.part_ml[piece(k) * 2 + 1] * exp2f(a.part_ml[piece(k) * 2] - M);
+  for (uint32_t d = lane; d < D; d += 64) {
+    float sum = 0.f;
+    for (uint32_t k = 0; k < np; ++k)
+      sum += a.part_o[piece(k) * D + d] * exp2f(a.part_ml[piece(k) * 2] - M);
+    orow[d] = L > 0.f ? sum / L : 0.f;
   }
 }
 
 }  // namespace
 
-bool attention_mfma_supported(const AttnLaunch& a) {
-  if (a.dtype != 1) return false;
-  if (a.head_dim != 64 && a.head_dim != 128 && a.head_dim != 256) return false;
-  return a.n_q_heads / a.n_kv_heads <= 16;
+bool attention_mfma_supported(uint32_t dtype, uint32_t n_q_heads, uint32_t n_kv_heads,
+                              uint32_t head_dim) {
+  if (dtype != 1) return false;
+  if (head_dim != 64 && head_dim != 128 && head_dim != 256) return false;
+  return n_q_heads / n_kv_heads <= 16;
+}
+
+uint32_t attention_runs_per_head(uint32_t n_kv_heads) {
+  // about 2048 wavefronts per launch: one full set of resident waves on 256 CUs
+  const uint32_t runs = 2048 / n_kv_heads;
+  return runs ? runs : 1;
+}
+
+hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s) {
+  attn_plan_kernel<<<dim3(1), dim3(1024), 0, s>>>(a.ctx, a.batch, a.max_pages, a.runs,
+                                                  const_cast<uint32_t*>(a.plan),
+                                                  const_cast<uint32_t*>(a.prefix),
+                                                  const_cast<uint2*>(a.desc));
+  return hipGetLastError();
 }
 
 hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s) {
-  const dim3 grid(a.n_kv_heads, a.max_chunks, a.batch);
+  const dim3 grid(a.n_kv_heads, a.runs);
   switch (a.head_dim) {
     case 64: attn_mfma_kernel<64><<<grid, dim3(64), 0, s>>>(a); break;
     case 128: attn_mfma_kernel<128><<<grid, dim3(64), 0, s>>>(a); break;
     default: attn_mfma_kernel<256><<<grid, dim3(64), 0, s>>>(a); break;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s) {
+  attn_merge_runs_kernel<<<dim3(a.n_q_heads, a.batch), dim3(64), 0, s>>>(a);
   return hipGetLastError();
 }
 

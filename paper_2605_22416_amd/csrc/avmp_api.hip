@@ -388,19 +388,33 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
 
   const avmp_config_t& c = p->cfg;
   const size_t eb = c.dtype == AVMP_F32 ? 4 : 2;
+  // work buffer: split-K partial results, plus the run plan of the matrix-core path
+  const bool mfma = avmp::attention_mfma_supported(c.dtype, c.n_q_heads, c.n_kv_heads, c.head_dim);
+  const uint32_t runs = avmp::attention_runs_per_head(c.n_kv_heads);
   const uint32_t worst = (st->max_pages + avmp::kChunkPages - 1) / avmp::kChunkPages;
   const uint32_t max_chunks = worst < avmp::kMaxChunks ? worst : avmp::kMaxChunks;
-  const size_t part_rows = size_t(st->batch) * max_chunks * c.n_q_heads;
+  const size_t part_rows = mfma ? size_t(runs) * 2 * c.n_q_heads
+                                : size_t(st->batch) * max_chunks * c.n_q_heads;
+  const size_t part_floats = part_rows * (size_t(c.head_dim) + 2);
+  const size_t plan_words = 4 + (size_t(st->batch) + 2) / 2 * 2 + size_t(runs) * 2;
   if (n_attn) {
-    rc = ensure_workspace(p, part_rows * (size_t(c.head_dim) + 2) * sizeof(float));
+    rc = ensure_workspace(p, (part_floats + plan_words) * sizeof(float));
     if (rc != AVMP_OK) return rc;
   }
+  uint32_t* plan_base = reinterpret_cast<uint32_t*>(p->ws + part_floats);
   const avmp::DevPools P = p->dev_view();
   uint32_t ia = 0, is = 0;
+  bool planned = false;
   for (uint32_t i = 0; i < st->n_layers; ++i) {
     if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) {
       avmp::AttnLaunch a{};
       a.P = P;
+      if (mfma) {
+        a.plan = plan_base;
+        a.prefix = plan_base + 4;
+        a.desc = reinterpret_cast<const uint2*>(plan_base + 4 + (size_t(st->batch) + 2) / 2 * 2);
+        a.runs = runs;
+      }
       a.handles = st->kv_handles + size_t(ia) * st->batch * st->max_pages;
       a.ctx = st->ctx;
       const size_t row = size_t(st->batch) * c.n_q_heads * c.head_dim;
@@ -415,6 +429,11 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.n_kv_heads = c.n_kv_heads;
       a.head_dim = c.head_dim;
       a.dtype = c.dtype;
+      if (mfma && !planned) {            // context lengths are the same for every layer
+        ProfScope scope(p, AVMP_K_TABLE, s);
+        HIP_TRY(avmp::launch_attention_plan(a, s));
+        planned = true;
+      }
       {
         ProfScope scope(p, AVMP_K_ATTENTION, s);
         HIP_TRY(avmp::launch_attention(a, s));

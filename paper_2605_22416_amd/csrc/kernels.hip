@@ -354,7 +354,7 @@ hipError_t launch_translate(const DevPools& P, const uint32_t* handles, uint32_t
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
-  if (attention_mfma_supported(a)) return launch_attention_mfma(a, s);
+  if (a.plan != nullptr) return launch_attention_mfma(a, s);
   const dim3 grid(a.n_q_heads, a.max_chunks, a.batch);
   if (a.dtype == 0)
     attn_generic_kernel<float><<<grid, dim3(64), 0, s>>>(a);
@@ -365,6 +365,7 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
 
 hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
+  if (a.plan != nullptr) return launch_attention_merge_runs(a, s);
   attn_merge_kernel<<<dim3(a.n_q_heads, a.batch), dim3(64), 0, s>>>(a);
   return hipGetLastError();
 }

@@ -21,6 +21,11 @@ struct AttnLaunch {
   uint32_t batch, max_pages, max_chunks;
   uint32_t n_q_heads, n_kv_heads, head_dim;
   uint32_t dtype;            // 0 f32, 1 bf16
+  // matrix-core path only: balanced runs (see attn_mfma.hip)
+  const uint32_t* plan;      // device [2]: total pages, pages per run
+  const uint32_t* prefix;    // device [batch + 1]: page prefix sums
+  const uint2* desc;         // device [runs]: each run's starting (request, page)
+  uint32_t runs;             // runs (wavefronts) per KV head
 };
 
 struct SsmLaunch {
@@ -38,8 +43,12 @@ struct SsmLaunch {
 
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 // matrix-core variant (attn_mfma.hip): bf16, head_dim 64/128/256, query group <= 16
-bool attention_mfma_supported(const AttnLaunch& a);
+bool attention_mfma_supported(uint32_t dtype, uint32_t n_q_heads, uint32_t n_kv_heads,
+                              uint32_t head_dim);
+uint32_t attention_runs_per_head(uint32_t n_kv_heads);
+hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s);   // once per decode step
 hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s);
+hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s);
 hipError_t launch_table_updates(uint32_t* table, const TableUpdate* upd, uint32_t n, hipStream_t s);
