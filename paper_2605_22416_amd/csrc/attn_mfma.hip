@@ -311,11 +311,45 @@ __global__ __launch_bounds__(64) void attn_merge_runs_kernel(AttnLaunch a) {
   auto piece = [&](uint32_t k) -> size_t {  // first piece starts the request (slot 1)
     return ((size_t(g) * a.runs + wa + k) * 2 + (k == 0 ? 1 : 0)) * Gq + head;
   };
+  if (np <= 64) {
+    // lane k holds piece k's statistics; weights are broadcast while the partial
+    // outputs are summed in piece order
+    float mk = -INFINITY, lk = 0.f;
+    if (lane < np) {
+      const size_t idx = piece(lane);
+      mk = a.part_ml[idx * 2];
+      lk = a.part_ml[idx * 2 + 1];
+    }
+    float M = mk;
+    for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float wgt = lane < np ? exp2f(mk - M) : 0.f;
+    float L = lk * wgt;
+    for (int o = 32; o; o >>= 1) L += __shfl_xor(L, o);
+    for (uint32_t d0 = 0; d0 < D; d0 += 64) {
+      const uint32_t d = d0 + lane;
+      float sum = 0.f;
+      uint32_t k = 0;
+      for (; k + 4 <= np; k += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = d < D ? a.part_o[piece(k + u) * D + d] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum += v[u] * __shfl(wgt, int(k + u));
+      }
+      for (; k < np; ++k) {
+        const float v = d < D ? a.part_o[piece(k) * D + d] : 0.f;
+        sum += v * __shfl(wgt, int(k));
+      }
+      if (d < D) orow[d] = L > 0.f ? sum / L : 0.f;
+    }
+    return;
+  }
+  // more than 64 pieces (one very long request in a small batch): plain loops
   float M = -INFINITY;
   for (uint32_t k = lane; k < np; k += 64) M = fmaxf(M, a.part_ml[piece(k) * 2]);
   for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
   float L = 0.f;
-  for (uint32_t k = 0; k < np; ++k)         // sequential: a fixed order for any piece count
+  for (uint32_t k = 0; k < np; ++k)
     L += a.part_ml[piece(k) * 2 + 1] * exp2f(a.part_ml[piece(k) * 2] - M);
   for (uint32_t d = lane; d < D; d += 64) {
     float sum = 0.f;

@@ -256,10 +256,13 @@ __device__ __forceinline__ float4 load4<uint16_t>(const uint16_t* p) {
                      __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
 }
 
-template <typename E, int THREADS, int ROWS>
+// NS: compile-time dstate (0 = read it from the launch); EXACT: headdim is a
+// multiple of the rows one pass covers, so no row needs a bounds test.
+template <typename E, int THREADS, int ROWS, int NS, bool EXACT>
 __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
   const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
-  const uint32_t H = a.heads, Pd = a.headdim, N = a.dstate;
+  const uint32_t H = a.heads, Pd = a.headdim;
+  const uint32_t N = NS ? uint32_t(NS) : a.dstate;
   const uint64_t off = translate_offset(a.P, a.handles[r], 1);
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
   if (off == ~0ull) {
@@ -280,10 +283,14 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
 
   for (uint32_t pbase = row0; pbase < Pd; pbase += rpi * ROWS) {
     float4 s[ROWS];
+    float xs[ROWS];
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
       const uint32_t p = pbase + k * rpi;
-      if (p < Pd) s[k] = load_stream(S + size_t(p) * N);
+      if (EXACT || p < Pd) {
+        s[k] = load_stream(S + size_t(p) * N);
+        xs[k] = load_elem<E>(xrow + p);
+      }
     }
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
@@ -292,8 +299,8 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
       // wavefront, but the shuffles below run on all lanes and only the
       // memory accesses are masked
       float part = 0.f;
-      if (p < Pd) {
-        const float dtx = dt * load_elem<E>(xrow + p);
+      if (EXACT || p < Pd) {
+        const float dtx = dt * xs[k];
         float4 v = s[k];
         v.x = decay * v.x + dtx * Bv.x;
         v.y = decay * v.y + dtx * Bv.y;
@@ -302,8 +309,10 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
         store_stream(S + size_t(p) * N, v);
         part = v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w;
       }
-      for (uint32_t o = lpr >> 1; o; o >>= 1) part += __shfl_xor(part, int(o));
-      if (p < Pd && col == 0) yrow[p] = part;
+#pragma unroll
+      for (uint32_t o = 32; o; o >>= 1)
+        if (o < lpr) part += __shfl_xor(part, int(o));
+      if ((EXACT || p < Pd) && col == 0) yrow[p] = part;
     }
   }
 }
@@ -375,12 +384,17 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   const dim3 grid(a.heads, a.batch);
   // a head's tile is headdim x dstate/4 16-byte accesses: big tiles get 1024 threads
   const bool big = uint64_t(a.headdim) * (a.dstate / 4) >= 1024;
+  // the Mamba-2 shape (dstate 128, headdim a multiple of 64) gets a kernel with
+  // compile-time row geometry and no bounds tests
+  const bool exact128 = a.dstate == 128 && a.headdim % 64 == 0;
   if (a.dtype == 0) {
-    if (big) ssm_update_kernel<float, 1024, 2><<<grid, dim3(1024), 0, s>>>(a);
-    else ssm_update_kernel<float, 256, 4><<<grid, dim3(256), 0, s>>>(a);
+    if (exact128) ssm_update_kernel<float, 1024, 2, 128, true><<<grid, dim3(1024), 0, s>>>(a);
+    else if (big) ssm_update_kernel<float, 1024, 2, 0, false><<<grid, dim3(1024), 0, s>>>(a);
+    else ssm_update_kernel<float, 256, 4, 0, false><<<grid, dim3(256), 0, s>>>(a);
   } else {
-    if (big) ssm_update_kernel<uint16_t, 1024, 2><<<grid, dim3(1024), 0, s>>>(a);
-    else ssm_update_kernel<uint16_t, 256, 4><<<grid, dim3(256), 0, s>>>(a);
+    if (exact128) ssm_update_kernel<uint16_t, 1024, 2, 128, true><<<grid, dim3(1024), 0, s>>>(a);
+    else if (big) ssm_update_kernel<uint16_t, 1024, 2, 0, false><<<grid, dim3(1024), 0, s>>>(a);
+    else ssm_update_kernel<uint16_t, 256, 4, 0, false><<<grid, dim3(256), 0, s>>>(a);
   }
   return hipGetLastError();
 }
