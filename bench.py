@@ -25,6 +25,23 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the SSM kernel at this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs scaled by the same counters' readings for the plain migration copy (summary under
+# profiles/).  Valid only for the kernel source it was measured on: reported as null otherwise.
+SSM_TRAFFIC = {"source_sha256_16": "1f97b82634f4b519", "batch": 64, "bytes_per_launch": 527263 * 1024}
+
+
+def ssm_traffic(batch):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "ssm_update.hip")
+    try:
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if digest != SSM_TRAFFIC["source_sha256_16"] or batch != SSM_TRAFFIC["batch"]:
+        return None
+    return SSM_TRAFFIC["bytes_per_launch"]
+
 
 def attention_bytes(spec, ctx):
     """Algorithmic bytes of one attention layer for one request: valid K/V tokens,
@@ -215,7 +232,7 @@ def main():
         a = kernels["ssm"]["GBps"]
         roofline = {"kernel": "ssm_update_kernel", "bound": "hbm", "achieved": a,
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                    "traffic": None, "bytes_per_launch": ssm_layer_bytes,
+                    "traffic": ssm_traffic(sc.batch), "bytes_per_launch": ssm_layer_bytes,
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
 
     # ---- migration sweep (outside the timed region): pages/s of capacity moved ----------

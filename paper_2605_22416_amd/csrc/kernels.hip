@@ -1,6 +1,6 @@
 // gfx950 kernels of the hybrid decode path: table maintenance, translation,
-// shape-generic paged GQA decode attention (vector ALU), the chunk merge, the
-// in-place SSM state update and the migration copy + remap.
+// shape-generic paged GQA decode attention (vector ALU), the chunk merge and the
+// migration copy + remap.
 #include "kernels.hpp"
 
 #include <cmath>
@@ -223,100 +223,6 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnLaunch a) {
   }
 }
 
-// ---------------------------------------------------------------------------
-// SSM single-token state update, in place.  One workgroup per (head, request):
-// the head's [P][N] fp32 tile (32 KiB at 64 x 128) is streamed once in and once
-// out with 16-byte accesses; a row's N values sit in N/4 adjacent lanes, which
-// also reduce y = sum_n S*C.  The state is touched exactly once per step, so
-// its loads and stores carry the non-temporal hint.  1024-thread workgroups
-// move a whole tile in one burst of loads followed by one burst of stores;
-// on MI355X that measured 6.3 TB/s against 5.2 TB/s for 256-thread groups.
-// ---------------------------------------------------------------------------
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float4 load_stream(const float* p) {
-  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void store_stream(float* p, float4 v) {
-  const f32x4 w = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(p));
-}
-
-template <typename E>
-__device__ __forceinline__ float4 load4(const E* p);
-template <>
-__device__ __forceinline__ float4 load4<float>(const float* p) {
-  return *reinterpret_cast<const float4*>(p);
-}
-template <>
-__device__ __forceinline__ float4 load4<uint16_t>(const uint16_t* p) {
-  const uint2 u = *reinterpret_cast<const uint2*>(p);
-  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u),
-                     __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xFFFF0000u));
-}
-
-// NS: compile-time dstate (0 = read it from the launch); EXACT: headdim is a
-// multiple of the rows one pass covers, so no row needs a bounds test.
-template <typename E, int THREADS, int ROWS, int NS, bool EXACT>
-__global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
-  const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
-  const uint32_t H = a.heads, Pd = a.headdim;
-  const uint32_t N = NS ? uint32_t(NS) : a.dstate;
-  const uint64_t off = translate_offset(a.P, a.handles[r], 1);
-  float* yrow = a.y + (size_t(r) * H + h) * Pd;
-  if (off == ~0ull) {
-    if (tid == 0) count_fault(a.P);
-    for (uint32_t p = tid; p < Pd; p += THREADS) yrow[p] = 0.f;
-    return;
-  }
-  const uint32_t lpr = N / 4;                  // lanes per row (power of two, <= 64)
-  const uint32_t col = tid & (lpr - 1);
-  const uint32_t row0 = tid / lpr;
-  const uint32_t rpi = THREADS / lpr;          // rows per pass of the workgroup
-  const float dt = a.dt[size_t(r) * H + h];
-  const float decay = expf(dt * a.A[h]);
-  const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
-  const float4 Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
-  const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
-  float* S = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N + 4 * col;
-
-  for (uint32_t pbase = row0; pbase < Pd; pbase += rpi * ROWS) {
-    float4 s[ROWS];
-    float xs[ROWS];
-#pragma unroll
-    for (int k = 0; k < ROWS; ++k) {
-      const uint32_t p = pbase + k * rpi;
-      if (EXACT || p < Pd) {
-        s[k] = load_stream(S + size_t(p) * N);
-        xs[k] = load_elem<E>(xrow + p);
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < ROWS; ++k) {
-      const uint32_t p = pbase + k * rpi;
-      // p < Pd is uniform over the lanes of a row and rows never straddle a
-      // wavefront, but the shuffles below run on all lanes and only the
-      // memory accesses are masked
-      float part = 0.f;
-      if (EXACT || p < Pd) {
-        const float dtx = dt * xs[k];
-        float4 v = s[k];
-        v.x = decay * v.x + dtx * Bv.x;
-        v.y = decay * v.y + dtx * Bv.y;
-        v.z = decay * v.z + dtx * Bv.z;
-        v.w = decay * v.w + dtx * Bv.w;
-        store_stream(S + size_t(p) * N, v);
-        part = v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w;
-      }
-#pragma unroll
-      for (uint32_t o = 32; o; o >>= 1)
-        if (o < lpr) part += __shfl_xor(part, int(o));
-      if ((EXACT || p < Pd) && col == 0) yrow[p] = part;
-    }
-  }
-}
-
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -376,26 +282,6 @@ hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
   if (a.plan != nullptr) return launch_attention_merge_runs(a, s);
   attn_merge_kernel<<<dim3(a.n_q_heads, a.batch), dim3(64), 0, s>>>(a);
-  return hipGetLastError();
-}
-
-hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
-  if (a.batch == 0) return hipSuccess;
-  const dim3 grid(a.heads, a.batch);
-  // a head's tile is headdim x dstate/4 16-byte accesses: big tiles get 1024 threads
-  const bool big = uint64_t(a.headdim) * (a.dstate / 4) >= 1024;
-  // the Mamba-2 shape (dstate 128, headdim a multiple of 64) gets a kernel with
-  // compile-time row geometry and no bounds tests
-  const bool exact128 = a.dstate == 128 && a.headdim % 64 == 0;
-  if (a.dtype == 0) {
-    if (exact128) ssm_update_kernel<float, 1024, 2, 128, true><<<grid, dim3(1024), 0, s>>>(a);
-    else if (big) ssm_update_kernel<float, 1024, 2, 0, false><<<grid, dim3(1024), 0, s>>>(a);
-    else ssm_update_kernel<float, 256, 4, 0, false><<<grid, dim3(256), 0, s>>>(a);
-  } else {
-    if (exact128) ssm_update_kernel<uint16_t, 1024, 2, 128, true><<<grid, dim3(1024), 0, s>>>(a);
-    else if (big) ssm_update_kernel<uint16_t, 1024, 2, 0, false><<<grid, dim3(1024), 0, s>>>(a);
-    else ssm_update_kernel<uint16_t, 256, 4, 0, false><<<grid, dim3(256), 0, s>>>(a);
-  }
   return hipGetLastError();
 }
 
