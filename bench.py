@@ -63,33 +63,15 @@ def ssm_bytes(spec):
 def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=64):
     """Times the CPU oracle, as it stands, on the first requests of the batch
     (all 32 layers each) until about budget_s seconds of work are done."""
-    import numpy as np
-    from oracle import avmp_oracle as orc
-    from paper_2605_22416_amd import inputs
-    shape = orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                      spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate)
+    from oracle.sampled import RequestReference
     done, elapsed, nbytes = [], 0.0, 0
     ref_o, ref_y = {}, {}
     for r in range(min(max_requests, sc.batch)):
-        n_pages = int(sc.n_pages[r])
-        arena = (n_pages * spec.n_attn + 2) * spec.kv_page_bytes + (spec.n_ssm + 1) * spec.ssm_block_bytes
-        op = orc.Pools(shape, arena, n_pages * spec.n_attn + 2, spec.n_ssm + 1)
-        kv = np.full((spec.n_attn, 1, n_pages), 0xFFFFFFFF, dtype=np.uint32)
-        for la in range(spec.n_attn):
-            kv[la, 0] = op.alloc(orc.POOL_KV, n_pages)[1]
-        ssm = np.asarray(op.alloc(orc.POOL_SSM, spec.n_ssm)[1], dtype=np.uint32).reshape(spec.n_ssm, 1)
-        for la in range(spec.n_attn):
-            for i in range(n_pages):
-                op.unit_view(int(kv[la, 0, i]))[:] = inputs.unit_content(spec, seed, 0, la, r, i)
-        for ls in range(spec.n_ssm):
-            op.unit_view(int(ssm[ls, 0]))[:] = inputs.unit_content(spec, seed, 1, ls, r, 0)
-        one = {k: (v if k == "A" else v[:, r: r + 1]) for k, v in inp.items()}
+        ref = RequestReference(spec, seed, r, int(sc.ctx[r]), bool(sc.fresh[r]))
         t0 = time.perf_counter()
-        o, y = op.decode_step(spec.layer_kinds, kv, sc.ctx[r: r + 1], one["q"], ssm, one["x"],
-                              one["dt"], one["A"], one["B"], one["C"])
+        ref_o[r], ref_y[r] = ref.step(inp)
         elapsed += time.perf_counter() - t0
         nbytes += spec.n_attn * attention_bytes(spec, sc.ctx[r]) + spec.n_ssm * ssm_bytes(spec)
-        ref_o[r], ref_y[r] = o[:, 0], y[:, 0]
         done.append(r)
         if elapsed >= budget_s and len(done) >= 2:
             break

@@ -38,15 +38,17 @@ def alloc_order(sc: inputs.Scenario):
     return calls
 
 
-def unit_jobs(sc: inputs.Scenario):
-    """(pool, layer, request, index) of every unit that starts with generated contents."""
+def unit_jobs(sc: inputs.Scenario, requests=None):
+    """(pool, layer, request, index) of every unit that starts with generated contents
+    (of the given requests only, if a list is given)."""
+    rs = range(sc.batch) if requests is None else list(requests)
     jobs = []
     for la in range(sc.spec.n_attn):
-        for r in range(sc.batch):
+        for r in rs:
             for i in range(int(sc.n_pages[r])):
                 jobs.append((inputs.POOL_KV, la, r, i))
     for ls in range(sc.spec.n_ssm):
-        for r in range(sc.batch):
+        for r in rs:
             if not sc.fresh[r]:
                 jobs.append((inputs.POOL_SSM, ls, r, 0))
     return jobs
@@ -112,11 +114,12 @@ class DeviceSession:
         pool, layer, r, i = job
         return int(self.kv[layer, r, i]) if pool == inputs.POOL_KV else int(self.ssm[layer, r])
 
-    def fill(self, transform: Optional[Callable] = None, scale_inputs=None, threads: int = 8):
-        """Write every live unit's generated contents.  transform(job, bytes) may
-        edit a unit's bytes before they are stored."""
+    def fill(self, transform: Optional[Callable] = None, scale_inputs=None, threads: int = 8,
+             requests=None):
+        """Write the generated contents of every live unit (or of the given requests'
+        units only).  transform(job, bytes) may edit a unit's bytes before they are stored."""
         sc = self.sc
-        jobs = unit_jobs(sc)
+        jobs = unit_jobs(sc, requests)
 
         def sink(i, data):
             if transform is not None:

@@ -265,3 +265,22 @@ def test_tiny_step_is_identical_after_migrating_four_free_pages():
         outs.append(p.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, inp["x"], inp["dt"],
                                   inp["A"], inp["B"], inp["C"]))
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_single_request_reference_equals_the_whole_batch_oracle():
+    """A request's outputs depend on its own units only: rebuilding it alone in
+    small pools gives the very same numbers as the oracle run on the whole batch."""
+    from oracle.sampled import RequestReference
+    spec = inputs.TINY
+    sc = inputs.make_scenario(spec, "tiny", 4, seed=1001)
+    p, kv, ssm = helpers.build_oracle(sc)
+    helpers.fill_oracle(p, sc, kv, ssm)
+    refs = [RequestReference(spec, 1001, r, int(sc.ctx[r])) for r in range(4)]
+    for step in range(2):
+        inp = inputs.step_inputs(spec, 4, seed=1001, step=step)
+        o, y = p.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, inp["x"], inp["dt"],
+                             inp["A"], inp["B"], inp["C"])
+        for r in range(4):
+            o1, y1 = refs[r].step(inp)
+            assert np.array_equal(o1, o[:, r]) and np.array_equal(y1, y[:, r])
+            assert np.array_equal(refs[r].state(0), p.unit_view(int(ssm[0, r])).view(np.float32).reshape(4, 32, 16))
