@@ -181,6 +181,48 @@ int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, vo
  * S <- a*S + dt*x*B[n] in place, y = sum_n S*C[n] with the updated S. */
 int avmp_decode_step(avmp_pools_t* pools, const avmp_step_t* step, void* stream);
 
+/* Rebalancing policy of Method, "Dynamic Pool Rebalancing" and Fig. 2.  A
+ * four-state machine (BALANCED, KV_PRESSURED / SSM_PRESSURED, REBALANCING) is
+ * evaluated only inside the capacity-error handler of avmp_alloc_auto:
+ * BALANCED -> X_PRESSURED when pool X's free fraction is below threshold_low;
+ * X_PRESSURED -> REBALANCING when the other pool's free fraction exceeds
+ * threshold_high and at least min_rebalance_interval_ops logical operations
+ * have passed since the last rebalance; REBALANCING -> BALANCED when the
+ * migration completes; X_PRESSURED -> BALANCED when X's free fraction recovers.
+ * One rebalance gives the starving pool up to migration_batch_size units
+ * (limited by the donor's free units).  Defaults: 0.05, 0.30, 128, 1000. */
+typedef struct avmp_policy {
+  double threshold_low;
+  double threshold_high;
+  uint32_t migration_batch_size;
+  uint32_t reserved;
+  uint64_t min_rebalance_interval_ops;
+} avmp_policy_t;
+
+enum { AVMP_BALANCED = 0, AVMP_KV_PRESSURED = 1, AVMP_SSM_PRESSURED = 2, AVMP_REBALANCING = 3 };
+
+typedef struct avmp_policy_state {
+  uint32_t state;                /* AVMP_BALANCED ... */
+  uint32_t has_rebalanced;
+  uint64_t last_rebalance_op;    /* value of the operation counter at the last rebalance */
+  uint64_t rebalance_count;
+  uint64_t oom_events;           /* avmp_alloc_auto calls that finally failed */
+} avmp_policy_state_t;
+
+/* Set the policy and reset the state machine.  AVMP_ERR_INVALID_ARG unless
+ * 0 <= threshold_low < threshold_high <= 1 and migration_batch_size >= 1 (the
+ * paper's validation check: low >= high has no defined transition semantics). */
+int avmp_policy_set(avmp_pools_t* pools, const avmp_policy_t* policy);
+int avmp_policy_state(const avmp_pools_t* pools, avmp_policy_state_t* out);
+
+/* allocate() with the capacity-error handler: like avmp_alloc, but when the pool
+ * is full the state machine above may migrate capacity from the other pool (on
+ * `stream`, as avmp_migrate) and the allocation is retried once.  With no donor
+ * it behaves exactly as avmp_alloc (static partition).  *donor_units_migrated
+ * (may be NULL) receives the number of units the other pool gave up, else 0. */
+int avmp_alloc_auto(avmp_pools_t* pools, int pool, uint32_t n, avmp_handle_t* out, void* stream,
+                    uint32_t* donor_units_migrated);
+
 /* Push queued table updates and zero fills to the device on `stream`. */
 int avmp_flush(avmp_pools_t* pools, void* stream);
 

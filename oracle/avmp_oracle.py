@@ -451,3 +451,97 @@ class Pools:
         o = np.stack(o) if o else np.zeros((0, len(ctx), sh.n_q_heads, sh.head_dim))
         y = np.stack(y) if y else np.zeros((0, len(ctx), sh.ssm_heads, sh.ssm_headdim))
         return o, y
+
+
+# ----------------------------------------------------------------------------
+# Rebalancing policy (Method, "Dynamic Pool Rebalancing", Fig. 2, and the
+# failure modes listed under Limitations).  A four-state machine whose
+# transitions are evaluated ONLY inside the CapacityError handler of
+# allocate(): BALANCED -> X_PRESSURED when x_free < threshold_low;
+# X_PRESSURED -> REBALANCING when the other pool's free fraction exceeds
+# threshold_high; REBALANCING -> BALANCED when the migration completes;
+# X_PRESSURED -> BALANCED when x's free fraction recovers.  Rebalancing is
+# throttled by the logical operation counter (at least
+# min_rebalance_interval_ops operations between migrations) and the step is
+# bounded by migration_batch_size.  With no donor above threshold_high the
+# allocator behaves as a static partition.
+#
+# Readings where the text is silent: migration_batch_size counts units of the
+# RECIPIENT pool (the step gives the starving pool up to B units, limited by
+# the donor's free units); one failing allocate() may take several transitions
+# in a row (BALANCED -> X_PRESSURED -> REBALANCING -> BALANCED); after a
+# migration the allocation is retried once.
+# ----------------------------------------------------------------------------
+BALANCED = 0
+KV_PRESSURED = 1
+SSM_PRESSURED = 2
+REBALANCING = 3
+
+
+@dataclass(frozen=True)
+class Policy:
+    threshold_low: float = 0.05
+    threshold_high: float = 0.30
+    migration_batch_size: int = 128
+    min_rebalance_interval_ops: int = 1000
+
+
+class Rebalancer:
+    def __init__(self, pools: Pools, policy: Policy = Policy()):
+        if not (0.0 <= policy.threshold_low < policy.threshold_high <= 1.0):
+            raise ValueError("threshold_low must be below threshold_high")
+        if policy.migration_batch_size < 1 or policy.min_rebalance_interval_ops < 0:
+            raise ValueError("bad migration_batch_size or min_rebalance_interval_ops")
+        self.pools = pools
+        self.policy = policy
+        self.state = BALANCED
+        self.last_rebalance_op: Optional[int] = None
+        self.rebalance_count = 0
+        self.oom_events = 0            # allocate() calls that finally failed
+
+    def free_fraction(self, pool: int) -> float:
+        cap = self.pools.capacity[pool]
+        return self.pools.free_count(pool) / cap if cap else 0.0
+
+    def allocate(self, pool: int, n: int) -> Tuple[int, List[int], int]:
+        """Returns (code, handles, donor units migrated by this call)."""
+        code, hs = self.pools.alloc(pool, n)
+        if code != ERR_CAPACITY:
+            return code, hs, 0
+        moved = self._capacity_error_handler(pool)
+        if moved:
+            code, hs = self.pools.alloc(pool, n)
+        if code == ERR_CAPACITY:
+            self.oom_events += 1
+        return code, hs, moved
+
+    def _capacity_error_handler(self, pool: int) -> int:
+        pol, p = self.policy, self.pools
+        other = 1 - pool
+        pressured = KV_PRESSURED if pool == POOL_KV else SSM_PRESSURED
+        # free recovers
+        if self.state == KV_PRESSURED and self.free_fraction(POOL_KV) >= pol.threshold_low:
+            self.state = BALANCED
+        if self.state == SSM_PRESSURED and self.free_fraction(POOL_SSM) >= pol.threshold_low:
+            self.state = BALANCED
+        if self.state == BALANCED and self.free_fraction(pool) < pol.threshold_low:
+            self.state = pressured
+        if self.state != pressured:
+            return 0
+        if not (self.free_fraction(other) > pol.threshold_high):
+            return 0                                   # no donor: static-partition behaviour
+        if self.last_rebalance_op is not None and \
+                p.ops - self.last_rebalance_op < pol.min_rebalance_interval_ops:
+            return 0                                   # throttled
+        need_bytes = pol.migration_batch_size * p.unit[pool] - p.gap
+        donor_units = max(0, -(-need_bytes // p.unit[other]))
+        donor_units = min(donor_units, p.free_count(other))
+        if donor_units == 0:
+            return 0
+        self.state = REBALANCING
+        res = p.migrate(other, donor_units)
+        assert res.code == OK
+        self.rebalance_count += 1
+        self.last_rebalance_op = p.ops
+        self.state = BALANCED                          # migration complete
+        return donor_units

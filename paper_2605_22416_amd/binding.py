@@ -100,6 +100,20 @@ class avmp_profile_t(C.Structure):
     _fields_ = [("ms", C.c_double * AVMP_K_COUNT), ("launches", C.c_uint64 * AVMP_K_COUNT)]
 
 
+class avmp_policy_t(C.Structure):
+    _fields_ = [("threshold_low", C.c_double), ("threshold_high", C.c_double),
+                ("migration_batch_size", C.c_uint32), ("reserved", C.c_uint32),
+                ("min_rebalance_interval_ops", C.c_uint64)]
+
+
+class avmp_policy_state_t(C.Structure):
+    _fields_ = [("state", C.c_uint32), ("has_rebalanced", C.c_uint32),
+                ("last_rebalance_op", C.c_uint64), ("rebalance_count", C.c_uint64),
+                ("oom_events", C.c_uint64)]
+
+
+AVMP_BALANCED, AVMP_KV_PRESSURED, AVMP_SSM_PRESSURED, AVMP_REBALANCING = range(4)
+
 _P = C.c_void_p
 lib.avmp_last_error.restype = C.c_char_p
 lib.avmp_last_error.argtypes = []
@@ -116,11 +130,15 @@ lib.avmp_resolve.argtypes = [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.
                              C.POINTER(C.c_uint64)]
 lib.avmp_stats.argtypes = [_P, C.POINTER(avmp_stats_t)]
 lib.avmp_device_faults.argtypes = [_P, _P, C.POINTER(C.c_uint64)]
+lib.avmp_policy_set.argtypes = [_P, C.POINTER(avmp_policy_t)]
+lib.avmp_policy_state.argtypes = [_P, C.POINTER(avmp_policy_state_t)]
+lib.avmp_alloc_auto.argtypes = [_P, C.c_int, C.c_uint32, _P, _P, C.POINTER(C.c_uint32)]
 lib.avmp_profile_enable.argtypes = [_P, C.c_int]
 lib.avmp_profile_read.argtypes = [_P, _P, C.POINTER(avmp_profile_t)]
 for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_alloc", "avmp_free",
            "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
-           "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read"):
+           "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read",
+           "avmp_policy_set", "avmp_policy_state", "avmp_alloc_auto"):
     getattr(lib, _f).restype = C.c_int
 
 
@@ -259,3 +277,28 @@ def avmp_profile_read(pools, stream=None):
     out = avmp_profile_t()
     rc = lib.avmp_profile_read(pools, _stream(stream), C.byref(out))
     return rc, {KERNEL_NAMES[k]: (out.ms[k], out.launches[k]) for k in range(AVMP_K_COUNT)}
+
+
+def avmp_policy_set(pools, threshold_low=0.05, threshold_high=0.30, migration_batch_size=128,
+                    min_rebalance_interval_ops=1000) -> int:
+    pol = avmp_policy_t(threshold_low, threshold_high, migration_batch_size, 0,
+                        min_rebalance_interval_ops)
+    return lib.avmp_policy_set(pools, C.byref(pol))
+
+
+def avmp_policy_state(pools) -> dict:
+    st = avmp_policy_state_t()
+    rc = lib.avmp_policy_state(pools, C.byref(st))
+    if rc != AVMP_OK:
+        raise RuntimeError(avmp_last_error())
+    return {"state": st.state, "has_rebalanced": bool(st.has_rebalanced),
+            "last_rebalance_op": st.last_rebalance_op, "rebalance_count": st.rebalance_count,
+            "oom_events": st.oom_events}
+
+
+def avmp_alloc_auto(pools, pool: int, n: int, stream=None):
+    """Returns (rc, handles or None, donor units migrated by this call)."""
+    out = np.empty(max(n, 1), dtype=np.uint32)
+    moved = C.c_uint32()
+    rc = lib.avmp_alloc_auto(pools, pool, n, out.ctypes.data, _stream(stream), C.byref(moved))
+    return rc, (out[:n] if rc == AVMP_OK else None), moved.value

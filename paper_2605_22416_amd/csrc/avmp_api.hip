@@ -94,6 +94,7 @@ struct avmp_pools {
   std::vector<avmp::TableUpdate> pending;
   std::vector<uint32_t> pending_zero;  // SSM slots to clear
   Staging staging;
+  avmp::Rebalancer rebalancer;
 
   // per-kernel timing: event pairs on the launch stream, summed at read time
   struct ProfRec {
@@ -320,6 +321,48 @@ int avmp_free(avmp_pools_t* p, const avmp_handle_t* handles, uint32_t n) {
   if (rc != AVMP_OK) return fail(rc, rc == AVMP_ERR_INVALID_HANDLE ? "stale or malformed handle" : "bad n");
   if (!p->has_device) p->pending.clear();
   return AVMP_OK;
+}
+
+int avmp_policy_set(avmp_pools_t* p, const avmp_policy_t* pol) {
+  if (p == nullptr || pol == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  if (!(pol->threshold_low >= 0.0 && pol->threshold_low < pol->threshold_high &&
+        pol->threshold_high <= 1.0))
+    return fail(AVMP_ERR_INVALID_ARG, "need 0 <= threshold_low < threshold_high <= 1");
+  if (pol->migration_batch_size < 1) return fail(AVMP_ERR_INVALID_ARG, "migration_batch_size < 1");
+  p->rebalancer = avmp::Rebalancer();
+  p->rebalancer.policy.threshold_low = pol->threshold_low;
+  p->rebalancer.policy.threshold_high = pol->threshold_high;
+  p->rebalancer.policy.migration_batch_size = pol->migration_batch_size;
+  p->rebalancer.policy.min_rebalance_interval_ops = pol->min_rebalance_interval_ops;
+  return AVMP_OK;
+}
+
+int avmp_policy_state(const avmp_pools_t* p, avmp_policy_state_t* out) {
+  if (p == nullptr || out == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  out->state = uint32_t(p->rebalancer.state);
+  out->has_rebalanced = p->rebalancer.has_rebalanced ? 1u : 0u;
+  out->last_rebalance_op = p->rebalancer.last_rebalance_op;
+  out->rebalance_count = p->rebalancer.rebalance_count;
+  out->oom_events = p->rebalancer.oom_events;
+  return AVMP_OK;
+}
+
+int avmp_alloc_auto(avmp_pools_t* p, int pool, uint32_t n, avmp_handle_t* out, void* stream,
+                    uint32_t* donor_units_migrated) {
+  if (donor_units_migrated) *donor_units_migrated = 0;
+  int rc = avmp_alloc(p, pool, n, out);
+  if (rc != AVMP_ERR_CAPACITY) return rc;
+  // the capacity-error handler: the only place where the state machine runs
+  const uint32_t donate = p->st.on_capacity_error(pool, &p->rebalancer);
+  if (donate != 0) {
+    const int mrc = avmp_migrate(p, 1 - pool, donate, stream, nullptr);
+    if (mrc != AVMP_OK) return mrc;       // cannot happen for a planned step; device errors only
+    p->st.rebalance_done(&p->rebalancer);
+    if (donor_units_migrated) *donor_units_migrated = donate;
+    rc = avmp_alloc(p, pool, n, out);
+  }
+  if (rc == AVMP_ERR_CAPACITY) ++p->rebalancer.oom_events;
+  return rc;
 }
 
 int avmp_flush(avmp_pools_t* p, void* stream) {

@@ -206,4 +206,36 @@ int PoolState::migrate(int donor, uint32_t n, std::vector<Move>* moves,
   return 0;
 }
 
+uint32_t PoolState::on_capacity_error(int pool, Rebalancer* rb) const {
+  const Policy& pol = rb->policy;
+  const int other = 1 - pool;
+  auto free_fraction = [&](int p) {
+    return capacity_[p] ? double(capacity_[p] - live_[p]) / double(capacity_[p]) : 0.0;
+  };
+  const int pressured = pool == 0 ? kKvPressured : kSsmPressured;
+  // "free recovers"
+  if (rb->state == kKvPressured && free_fraction(0) >= pol.threshold_low) rb->state = kBalanced;
+  if (rb->state == kSsmPressured && free_fraction(1) >= pol.threshold_low) rb->state = kBalanced;
+  if (rb->state == kBalanced && free_fraction(pool) < pol.threshold_low) rb->state = pressured;
+  if (rb->state != pressured) return 0;
+  if (!(free_fraction(other) > pol.threshold_high)) return 0;       // no donor: static behaviour
+  if (rb->has_rebalanced && c_.ops - rb->last_rebalance_op < pol.min_rebalance_interval_ops)
+    return 0;                                                        // throttled
+  const uint64_t want = uint64_t(pol.migration_batch_size) * g_.unit[pool];
+  if (want <= gap_) return 0;
+  uint64_t donor_units = (want - gap_ + g_.unit[other] - 1) / g_.unit[other];
+  const uint64_t donor_free = capacity_[other] - live_[other];
+  if (donor_units > donor_free) donor_units = donor_free;
+  if (donor_units == 0) return 0;
+  rb->state = kRebalancing;
+  return uint32_t(donor_units);
+}
+
+void PoolState::rebalance_done(Rebalancer* rb) const {
+  ++rb->rebalance_count;
+  rb->has_rebalanced = true;
+  rb->last_rebalance_op = c_.ops;
+  rb->state = kBalanced;                                             // migration complete
+}
+
 }  // namespace avmp

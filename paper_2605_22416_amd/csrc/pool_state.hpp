@@ -60,6 +60,27 @@ struct ShapeArgs {
 // Returns false if the shape is unusable (zero sizes, more than 2^30 slots).
 bool compute_geometry(const ShapeArgs& s, uint64_t arena_bytes, Geometry* g);
 
+// Rebalancing policy of Method, "Dynamic Pool Rebalancing" / Fig. 2: thresholds
+// on per-pool free fractions, a bound on the migration step and a throttle on the
+// logical operation counter.  Defaults are the paper's.
+struct Policy {
+  double threshold_low = 0.05;
+  double threshold_high = 0.30;
+  uint32_t migration_batch_size = 128;        // units of the recipient pool per rebalance
+  uint64_t min_rebalance_interval_ops = 1000;
+};
+
+enum PressureState { kBalanced = 0, kKvPressured = 1, kSsmPressured = 2, kRebalancing = 3 };
+
+struct Rebalancer {
+  Policy policy;
+  int state = kBalanced;
+  bool has_rebalanced = false;
+  uint64_t last_rebalance_op = 0;
+  uint64_t rebalance_count = 0;
+  uint64_t oom_events = 0;                    // allocations that finally failed
+};
+
 class PoolState {
  public:
   // rank[p] may be empty (identity).  Returns false on invalid arguments.
@@ -73,6 +94,14 @@ class PoolState {
   int migrate(int donor, uint32_t n, std::vector<Move>* moves, std::vector<TableUpdate>* upd,
               uint32_t* gain, uint64_t* wasted);
   bool resolve(uint32_t h, uint32_t* pool, uint32_t* slot, uint64_t* off) const;
+
+  // The CapacityError handler of allocate(): runs the state machine for a failed
+  // allocation in `pool` and returns how many units the OTHER pool should donate
+  // now (0: no donor above threshold_high, throttled, or not pressured).  When it
+  // returns non-zero the state is kRebalancing; call rebalance_done() after the
+  // migration.
+  uint32_t on_capacity_error(int pool, Rebalancer* rb) const;
+  void rebalance_done(Rebalancer* rb) const;
 
   uint64_t byte_offset(int pool, uint32_t slot) const {
     return pool == 0 ? uint64_t(slot) * g_.unit[0] : g_.usable - (uint64_t(slot) + 1) * g_.unit[1];

@@ -320,3 +320,41 @@ def test_decode_step_replayed_from_a_hip_graph_matches_eager_steps():
     assert av.avmp_device_faults(graphed.p) == (av.AVMP_OK, 0)
     eager.close()
     graphed.close()
+
+
+def test_alloc_auto_rebalances_on_device_and_keeps_contents():
+    """A capacity error in the KV pool with slack in the SSM pool: the handler
+    migrates SSM capacity on the device (live blocks are copied), the retry
+    succeeds, handles and contents match the oracle's policy run, and the
+    decode step still matches."""
+    from paper_2605_22416_amd import binding as av
+    spec = inputs.TINY
+    sc = inputs.make_scenario(spec, "tiny", 4, seed=51, ctx=[64, 64, 64, 64])
+    sc.kv_capacity, sc.ssm_capacity = 17, 24          # 16 live pages of 17; 4 live blocks of 24
+    sc.arena_bytes = 17 * spec.kv_page_bytes + 24 * spec.ssm_block_bytes
+    prng = np.random.default_rng(3)
+    sc.slot_rank = [prng.permutation(sc.arena_bytes // spec.kv_page_bytes).astype(np.uint32),
+                    prng.permutation(sc.arena_bytes // spec.ssm_block_bytes).astype(np.uint32)]
+    op, g, kv, ssm = _both(sc, poison=True)
+    policy = dict(threshold_low=0.1, threshold_high=0.3, migration_batch_size=6,
+                  min_rebalance_interval_ops=0)
+    rb = orc.Rebalancer(op, orc.Policy(**policy))
+    assert av.avmp_policy_set(g.p, **policy) == av.AVMP_OK
+    extra = []
+    for n in (1, 3, 2, 9):
+        oc, oh, om = rb.allocate(0, n)
+        lc, lh, lm = av.avmp_alloc_auto(g.p, 0, n)
+        assert (oc, om) == (lc, lm) and (oc != orc.OK or list(lh) == oh)
+        extra.extend(oh)
+        assert av.avmp_stats(g.p) == op.stats()
+    assert rb.rebalance_count >= 2 and op.units_copied > 0
+    st = av.avmp_policy_state(g.p)
+    assert (st["state"], st["rebalance_count"], st["oom_events"]) == (rb.state, rb.rebalance_count, rb.oom_events)
+    _check_translation(g, op, list(kv.reshape(-1)) + list(ssm.reshape(-1)) + extra)
+    for h in list(ssm.reshape(-1)) + [int(kv[0, 2, 1])]:
+        assert np.array_equal(g.read_unit(int(h)), op.unit_view(int(h)))
+    inp = inputs.step_inputs(spec, 4, seed=51)
+    ref_o, ref_y = _oracle_step(op, sc, kv, ssm, inp)
+    o, y = g.step(inp)
+    _check_outputs(spec, o, y, ref_o, ref_y, "after rebalancing")
+    g.close()
