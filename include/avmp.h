@@ -113,9 +113,9 @@ typedef struct avmp_stats {
 } avmp_stats_t;
 
 /* One hybrid decode step: layers in model order; per-kind arrays are indexed by
- * the layer's ordinal among layers of its kind.  The step does not append a
- * token: ctx counts tokens already resident.  Two requests of one batch must
- * not name the same SSM handle. */
+ * the layer's ordinal among layers of its kind.  ctx counts tokens already
+ * resident; the step appends the new token only if k_new / v_new are given.
+ * Two requests of one batch must not name the same SSM handle. */
 typedef struct avmp_step {
   uint32_t batch;
   uint32_t n_layers;
@@ -133,6 +133,13 @@ typedef struct avmp_step {
   const void* B;                     /* device [n_ssm][batch][N] elements */
   const void* C;                     /* device [n_ssm][batch][N] elements */
   float* y;                          /* device [n_ssm][batch][H][P] fp32 out */
+  /* Optional append of the step's new token (both NULL: no append).  When given,
+   * each attention layer first writes the token's K and V rows into token slot
+   * ctx % 16 of page ctx / 16 of every request (the caller has allocated that
+   * page and placed its handle in kv_handles), then attends over ctx + 1 tokens.
+   * ctx itself is not modified. */
+  const void* k_new;                 /* device [n_attn][batch][n_kv_heads][head_dim] elements */
+  const void* v_new;                 /* device [n_attn][batch][n_kv_heads][head_dim] elements */
 } avmp_step_t;
 
 /* Size arithmetic of Method, "Asymmetric Virtual Page Table": KV page =

@@ -16,8 +16,9 @@ geometry arithmetic and its own page-layout index formulas.
 
 Parity pins: every function here is pinned by tests in tests/test_oracle_*.py
 (worked example of Fig. 1, closed-form unit sizes, dense attention through a
-library routine, unrolled recurrence closed form, two-counter capacity model,
-migration conservation laws).  Not pinned, because the paper's harness and
+library routine - also for the append path -, unrolled recurrence closed form,
+two-counter capacity model, migration conservation laws, the paper's default
+policy parameters and each edge of Fig. 2).  Not pinned, because the paper's harness and
 traces are not available: the paper's OOM counts, goodput and bootstrap CIs
 ("parity unpinned"; not attempted).
 
@@ -429,20 +430,40 @@ class Pools:
         return y
 
     # ---- one hybrid decode step ------------------------------------------------
+    def append_token(self, handles: np.ndarray, ctx: np.ndarray, k_new: np.ndarray,
+                     v_new: np.ndarray) -> None:
+        """Append-only KV behaviour (Background, "KV Cache and SSM State Management"):
+        request r's new token goes to token slot ctx[r] % T of its page ctx[r] // T,
+        whose handle the caller has already placed in handles[r].  k_new, v_new:
+        [batch][Hkv][D] in the element dtype."""
+        T = self.shape.page_tokens
+        for r in range(len(ctx)):
+            t = int(ctx[r])
+            self.write_kv_token(int(handles[r, t // T]), t % T, k_new[r], v_new[r])
+
     def decode_step(self, layer_kinds: Sequence[int], kv_handles: np.ndarray, ctx: np.ndarray,
                     q: np.ndarray, ssm_handles: np.ndarray, x: np.ndarray, dt: np.ndarray,
-                    A: np.ndarray, B: np.ndarray, C: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+                    A: np.ndarray, B: np.ndarray, C: np.ndarray,
+                    k_new: Optional[np.ndarray] = None,
+                    v_new: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
         """Layers in model order (0 = attention, 1 = SSM).  Per-kind arrays are
         indexed by the layer's ordinal among layers of its kind:
         kv_handles [n_attn][batch][max_pages], q [n_attn][batch][Hq][D],
         ssm_handles [n_ssm][batch], x [n_ssm][batch][H][P], dt [n_ssm][batch][H],
-        A [n_ssm][H], B, C [n_ssm][batch][N].  The step does not append a token:
-        ctx counts tokens already resident.  Returns (o [n_attn]..., y [n_ssm]...)."""
+        A [n_ssm][H], B, C [n_ssm][batch][N].  ctx counts tokens already resident.
+        If k_new, v_new ([n_attn][batch][Hkv][D]) are given, each attention layer
+        first appends the new token and then attends over ctx + 1 tokens.
+        Returns (o [n_attn]..., y [n_ssm]...)."""
         o, y = [], []
         ia = iss = 0
+        ctx = np.asarray(ctx)
         for kind in layer_kinds:
             if kind == 0:
-                o.append(self.paged_attention(kv_handles[ia], ctx, q[ia]))
+                if k_new is not None:
+                    self.append_token(kv_handles[ia], ctx, k_new[ia], v_new[ia])
+                    o.append(self.paged_attention(kv_handles[ia], ctx + 1, q[ia]))
+                else:
+                    o.append(self.paged_attention(kv_handles[ia], ctx, q[ia]))
                 ia += 1
             else:
                 y.append(self.ssm_step(ssm_handles[iss], x[iss], dt[iss], A[iss], B[iss], C[iss]))

@@ -88,7 +88,7 @@ class avmp_step_t(C.Structure):
                 ("max_pages", C.c_uint32), ("kv_handles", C.c_void_p), ("ctx", C.c_void_p),
                 ("q", C.c_void_p), ("o", C.c_void_p), ("ssm_handles", C.c_void_p),
                 ("x", C.c_void_p), ("dt", C.c_void_p), ("A", C.c_void_p), ("B", C.c_void_p),
-                ("C", C.c_void_p), ("y", C.c_void_p)]
+                ("C", C.c_void_p), ("y", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p)]
 
 
 AVMP_K_ATTENTION, AVMP_K_ATTENTION_MERGE, AVMP_K_SSM, AVMP_K_MIGRATE_COPY, AVMP_K_TABLE = range(5)
@@ -221,7 +221,7 @@ def avmp_migrate(pools, donor_pool: int, n_donor_units: int, stream=None):
 
 
 def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles, ctx, q, o,
-              ssm_handles, x, dt, A, B, Cm, y):
+              ssm_handles, x, dt, A, B, Cm, y, k_new=None, v_new=None):
     """Returns (avmp_step_t, keepalive).  Tensors must stay alive until the step has run."""
     st = avmp_step_t()
     kinds = np.ascontiguousarray(layer_kinds, dtype=np.uint8)
@@ -230,7 +230,8 @@ def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles
     st.kv_handles, st.ctx, st.q, st.o = _ptr(kv_handles), _ptr(ctx), _ptr(q), _ptr(o)
     st.ssm_handles, st.x, st.dt, st.A = _ptr(ssm_handles), _ptr(x), _ptr(dt), _ptr(A)
     st.B, st.C, st.y = _ptr(B), _ptr(Cm), _ptr(y)
-    return st, (kinds, kv_handles, ctx, q, o, ssm_handles, x, dt, A, B, Cm, y)
+    st.k_new, st.v_new = _ptr(k_new), _ptr(v_new)
+    return st, (kinds, kv_handles, ctx, q, o, ssm_handles, x, dt, A, B, Cm, y, k_new, v_new)
 
 
 def avmp_decode_step(pools, step: avmp_step_t, stream=None) -> int:

@@ -80,6 +80,7 @@ __device__ __forceinline__ uint32_t pages_of(uint32_t ctx, uint32_t max_pages) {
 // plan[0] = total pages, plan[1] = pages per run (ipw).
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restrict__ ctx, uint32_t batch,
                                                          uint32_t max_pages, uint32_t runs,
+                                                         uint32_t append,
                                                          uint32_t* __restrict__ plan,
                                                          uint32_t* __restrict__ prefix,
                                                          uint2* __restrict__ desc) {
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
   const uint32_t seg = (batch + 1023) / 1024;
   const uint32_t lo = min(batch, tid * seg), hi = min(batch, lo + seg);
   uint32_t local = 0;
-  for (uint32_t r = lo; r < hi; ++r) local += pages_of(ctx[r], max_pages);
+  for (uint32_t r = lo; r < hi; ++r) local += pages_of(attended_tokens(ctx, r, append), max_pages);
   sums[tid] = local;
   __syncthreads();
   for (uint32_t off = 1; off < 1024; off <<= 1) {          // inclusive scan
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
   uint32_t run = sums[tid] - local;                         // exclusive start of this segment
   for (uint32_t r = lo; r < hi; ++r) {
     prefix[r] = run;
-    run += pages_of(ctx[r], max_pages);
+    run += pages_of(attended_tokens(ctx, r, append), max_pages);
   }
   const uint32_t total = sums[1023];
   const uint32_t ipw = total == 0 ? 1 : (total + runs - 1) / runs;
@@ -145,13 +146,14 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
   const size_t vslab_off = size_t(G) * D * 32 + size_t(g) * D * 32;   // bytes: [D][16] bf16
 
   while (item < item_end && r < a.batch) {
-    const uint32_t n_pages = pages_of(a.ctx[r], a.max_pages);
+    const uint32_t n_ctx = attended_tokens(a.ctx, r, a.append);
+    const uint32_t n_pages = pages_of(n_ctx, a.max_pages);
     if (page >= n_pages) {             // request without pages (or exhausted): next one
       ++r;
       page = 0;
       continue;
     }
-    const uint32_t n_tok = min(a.ctx[r], n_pages * 16u);
+    const uint32_t n_tok = min(n_ctx, n_pages * 16u);
     const uint32_t p0 = page;
     const uint32_t p1 = uint32_t(min(uint64_t(n_pages), uint64_t(page) + (item_end - item)));
 
@@ -298,7 +300,8 @@ __global__ __launch_bounds__(64) void attn_merge_runs_kernel(AttnLaunch a) {
   const uint32_t D = a.head_dim, Hq = a.n_q_heads, Gq = Hq / a.n_kv_heads;
   const uint32_t g = j / Gq, head = j % Gq;
   float* orow = a.o + (size_t(r) * Hq + j) * D;
-  if (j == 0 && lane == 0 && uint64_t(a.ctx[r]) > uint64_t(a.max_pages) * 16u) count_fault(a.P);
+  if (j == 0 && lane == 0 && uint64_t(attended_tokens(a.ctx, r, a.append)) > uint64_t(a.max_pages) * 16u)
+    count_fault(a.P);
   const uint32_t start = a.prefix[r], end = a.prefix[r + 1];
   if (start == end) {                       // no resident tokens: zero row
     for (uint32_t d = lane; d < D; d += 64) orow[d] = 0.f;
@@ -375,7 +378,7 @@ uint32_t attention_runs_per_head(uint32_t n_kv_heads) {
 }
 
 hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s) {
-  attn_plan_kernel<<<dim3(1), dim3(1024), 0, s>>>(a.ctx, a.batch, a.max_pages, a.runs,
+  attn_plan_kernel<<<dim3(1), dim3(1024), 0, s>>>(a.ctx, a.batch, a.max_pages, a.runs, a.append,
                                                   const_cast<uint32_t*>(a.plan),
                                                   const_cast<uint32_t*>(a.prefix),
                                                   const_cast<uint2*>(a.desc));

@@ -421,6 +421,9 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
   if (n_attn && st->batch &&
       (!st->kv_handles || !st->ctx || !st->q || !st->o || st->max_pages == 0))
     return fail(AVMP_ERR_INVALID_ARG, "attention layers need kv_handles, ctx, q, o, max_pages");
+  if ((st->k_new == nullptr) != (st->v_new == nullptr))
+    return fail(AVMP_ERR_INVALID_ARG, "k_new and v_new go together");
+  const bool append = st->k_new != nullptr;
   if (n_ssm && st->batch &&
       (!st->ssm_handles || !st->x || !st->dt || !st->A || !st->B || !st->C || !st->y))
     return fail(AVMP_ERR_INVALID_ARG, "SSM layers need ssm_handles, x, dt, A, B, C, y");
@@ -472,6 +475,14 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.n_kv_heads = c.n_kv_heads;
       a.head_dim = c.head_dim;
       a.dtype = c.dtype;
+      if (append) {
+        const size_t kvrow = size_t(st->batch) * c.n_kv_heads * c.head_dim * eb;
+        a.append = 1;
+        a.k_new = static_cast<const char*>(st->k_new) + size_t(ia) * kvrow;
+        a.v_new = static_cast<const char*>(st->v_new) + size_t(ia) * kvrow;
+        ProfScope scope(p, AVMP_K_TABLE, s);
+        HIP_TRY(avmp::launch_kv_append(a, s));
+      }
       if (mfma && !planned) {            // context lengths are the same for every layer
         ProfScope scope(p, AVMP_K_TABLE, s);
         HIP_TRY(avmp::launch_attention_plan(a, s));

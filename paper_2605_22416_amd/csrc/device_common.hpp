@@ -52,6 +52,12 @@ __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t* p) {
   return bf16_bits_to_float(*p);
 }
 
+// Tokens a request attends over: its resident tokens, plus the one the step appends.
+__device__ __forceinline__ uint32_t attended_tokens(const uint32_t* ctx, uint32_t r, uint32_t append) {
+  const uint32_t n = ctx[r];
+  return n > 0xFFFFFFFFu - append ? n : n + append;
+}
+
 // Split of a request's pages into chunks processed by different wavefronts and
 // merged afterwards.  It depends on the request's page count only, never on
 // physical placement, so results are identical under any placement and across

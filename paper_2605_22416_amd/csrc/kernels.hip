@@ -76,6 +76,38 @@ __global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t*
 }
 
 // ---------------------------------------------------------------------------
+// KV append: the new token's K and V rows go into token slot ctx % 16 of page
+// ctx / 16 (append-only KV behaviour: Background, "KV Cache and SSM State
+// Management").  The caller has allocated that page; the in-page layout is the
+// one the attention kernels read.  One workgroup per request.
+// ---------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void kv_append_kernel(AttnLaunch a) {
+  const uint32_t r = blockIdx.x, tid = threadIdx.x;
+  const uint32_t t = a.ctx[r];
+  const uint32_t page = t / 16, slot = t % 16;
+  if (page >= a.max_pages) {
+    if (tid == 0) count_fault(a.P);
+    return;
+  }
+  const uint64_t off = translate_offset(a.P, a.handles[size_t(r) * a.max_pages + page], 0);
+  if (off == ~0ull) {
+    if (tid == 0) count_fault(a.P);
+    return;
+  }
+  const uint32_t D = a.head_dim, G = a.n_kv_heads;
+  constexpr uint32_t X = 16 / sizeof(E);
+  E* pg = reinterpret_cast<E*>(a.P.arena + off);
+  const E* kn = static_cast<const E*>(a.k_new) + size_t(r) * G * D;
+  const E* vn = static_cast<const E*>(a.v_new) + size_t(r) * G * D;
+  for (uint32_t i = tid; i < G * D; i += 256) {
+    const uint32_t g = i / D, d = i % D;
+    pg[((size_t(g) * (D / X) + d / X) * 16 + slot) * X + d % X] = kn[i];
+    pg[size_t(G) * 16 * D + (size_t(g) * D + d) * 16 + slot] = vn[i];
+  }
+}
+
+// ---------------------------------------------------------------------------
 // shape-generic paged GQA decode attention: one wavefront per (query head,
 // chunk, request).  Lane = (token t = lane%16, dim quarter = lane/16) for the
 // scores; lane = dim for the weighted sum of V.  Online softmax in the log2
@@ -86,7 +118,7 @@ __global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t*
 // max_pages pages is the caller's mistake; it is clamped (and counted as a
 // fault by the merge kernel) so that the handle row is never read past its end.
 __device__ __forceinline__ uint32_t resident_tokens(const AttnLaunch& a, uint32_t r) {
-  const uint32_t n = a.ctx[r];
+  const uint32_t n = attended_tokens(a.ctx, r, a.append);
   const uint64_t room = uint64_t(a.max_pages) * 16u;
   return n > room ? uint32_t(room) : n;
 }
@@ -180,7 +212,8 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnLaunch a) {
 // function of the logical batch alone).  One wavefront per (query head, request).
 __global__ __launch_bounds__(64) void attn_merge_kernel(AttnLaunch a) {
   const uint32_t j = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
-  if (j == 0 && lane == 0 && uint64_t(a.ctx[r]) > uint64_t(a.max_pages) * 16u) count_fault(a.P);
+  if (j == 0 && lane == 0 && uint64_t(attended_tokens(a.ctx, r, a.append)) > uint64_t(a.max_pages) * 16u)
+    count_fault(a.P);
   const uint32_t n_pages = (resident_tokens(a, r) + 15) / 16;
   const uint32_t nch = chunk_count_for(n_pages);
   const uint32_t D = a.head_dim, Hq = a.n_q_heads;
@@ -264,6 +297,15 @@ hipError_t launch_translate(const DevPools& P, const uint32_t* handles, uint32_t
                             hipStream_t s) {
   if (n == 0) return hipSuccess;
   translate_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(P, handles, n, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_append(const AttnLaunch& a, hipStream_t s) {
+  if (a.batch == 0) return hipSuccess;
+  if (a.dtype == 0)
+    kv_append_kernel<float><<<dim3(a.batch), dim3(256), 0, s>>>(a);
+  else
+    kv_append_kernel<uint16_t><<<dim3(a.batch), dim3(256), 0, s>>>(a);
   return hipGetLastError();
 }
 

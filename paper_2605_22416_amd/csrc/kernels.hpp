@@ -21,6 +21,9 @@ struct AttnLaunch {
   uint32_t batch, max_pages, max_chunks;
   uint32_t n_q_heads, n_kv_heads, head_dim;
   uint32_t dtype;            // 0 f32, 1 bf16
+  uint32_t append;           // 1: the step appended one token, attend over ctx + 1 tokens
+  const void* k_new;         // device [batch][Hkv][D] (append only)
+  const void* v_new;         // device [batch][Hkv][D] (append only)
   // matrix-core path only: balanced runs (see attn_mfma.hip)
   const uint32_t* plan;      // device [2]: total pages, pages per run
   const uint32_t* prefix;    // device [batch + 1]: page prefix sums
@@ -41,6 +44,7 @@ struct SsmLaunch {
   uint32_t dtype;
 };
 
+hipError_t launch_kv_append(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 // matrix-core variant (attn_mfma.hip): bf16, head_dim 64/128/256, query group <= 16
 bool attention_mfma_supported(uint32_t dtype, uint32_t n_q_heads, uint32_t n_kv_heads,

@@ -197,6 +197,16 @@ def step_inputs(spec: ModelSpec, batch: int, seed: int, step: int = 0,
     return {"q": q, "x": x, "dt": dt, "A": A, "B": B, "C": C}
 
 
+def new_token_kv(spec: ModelSpec, batch: int, seed: int, step: int = 0,
+                 scale_inputs: Optional[bool] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """K and V rows of the token a step appends: [n_attn][batch][Hkv][D] each."""
+    rng = np.random.default_rng([seed, 4, step])
+    sc = spec.scale_inputs if scale_inputs is None else scale_inputs
+    s = 1.0 / math.sqrt(spec.head_dim) if sc else 1.0
+    shape = (spec.n_attn, batch, spec.n_kv_heads, spec.head_dim)
+    return elements(rng, shape, s, spec.dtype), elements(rng, shape, s, spec.dtype)
+
+
 # ----------------------------------------------------------------------------
 # unit contents: a pure function of (seed, pool, layer ordinal, request, index)
 # so that any single page or block can be regenerated without the whole arena

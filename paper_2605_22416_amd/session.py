@@ -130,25 +130,28 @@ class DeviceSession:
         torch.cuda.synchronize()
 
     # ---- decode steps ------------------------------------------------------------
-    def prepare_step(self, inp: Dict[str, np.ndarray]):
-        """Upload one step's activations, allocate outputs, build the descriptor."""
+    def prepare_step(self, inp: Dict[str, np.ndarray], k_new=None, v_new=None):
+        """Upload one step's activations (and the appended token's K, V rows, if
+        given), allocate outputs, build the descriptor."""
         sc, spec = self.sc, self.sc.spec
         d = {k: to_dev(v) for k, v in inp.items()}
+        kn = to_dev(k_new) if k_new is not None else None
+        vn = to_dev(v_new) if v_new is not None else None
         o = torch.full((spec.n_attn, sc.batch, spec.n_q_heads, spec.head_dim), float("nan"),
                        dtype=torch.float32, device=DEV)
         y = torch.full((spec.n_ssm, sc.batch, spec.ssm_heads, spec.ssm_headdim), float("nan"),
                        dtype=torch.float32, device=DEV)
         st, keep = av.make_step(sc.batch, spec.layer_kinds, self.kv.shape[2], self.kv_dev,
                                 self.ctx_dev, d["q"], o, self.ssm_dev, d["x"], d["dt"], d["A"],
-                                d["B"], d["C"], y)
+                                d["B"], d["C"], y, kn, vn)
         return st, keep, o, y
 
     def launch(self, st, stream=None):
         self._ok(av.avmp_decode_step(self.p, st, stream))
 
-    def step(self, inp: Dict[str, np.ndarray], stream=None):
+    def step(self, inp: Dict[str, np.ndarray], stream=None, k_new=None, v_new=None):
         """One decode step; returns (o, y) as numpy float32 and checks the fault counter."""
-        st, keep, o, y = self.prepare_step(inp)
+        st, keep, o, y = self.prepare_step(inp, k_new, v_new)
         self.launch(st, stream)
         torch.cuda.synchronize()
         rc, faults = av.avmp_device_faults(self.p)

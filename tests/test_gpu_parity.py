@@ -358,3 +358,46 @@ def test_alloc_auto_rebalances_on_device_and_keeps_contents():
     o, y = g.step(inp)
     _check_outputs(spec, o, y, ref_o, ref_y, "after rebalancing")
     g.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_loop_with_kv_append_and_page_allocation(dtype):
+    """A real decode loop: every step appends the new token's K/V (allocating a
+    page per attention layer when a request crosses a 16-token boundary, which
+    is where a capacity error would fire), attends over ctx + 1 tokens and
+    updates the SSM state; 20 steps against the oracle, then the appended pages
+    are compared byte for byte."""
+    from paper_2605_22416_amd import binding as av
+    base = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    spec = inputs.ModelSpec("append_" + dtype, dtype, 16, base.n_q_heads, base.n_kv_heads, base.head_dim,
+                            8, 16, 32, (inputs.SSM, inputs.ATTN, inputs.SSM), base.scale_inputs)
+    ctx0 = [0, 1, 15, 16, 127, 130, 250]
+    sc = inputs.make_scenario(spec, "uniform_short", len(ctx0), seed=61, ctx=ctx0, headroom=3.0)
+    op, g, kv, ssm = _both(sc, poison=True)
+    grow = 3                                   # room for 20 more tokens per request
+    kv = np.pad(kv, ((0, 0), (0, 0), (0, grow)), constant_values=0xFFFFFFFF)
+    g.kv = kv.copy()
+    ctx = np.array(ctx0, dtype=np.uint32)
+    for step in range(20):
+        for r in range(len(ctx)):
+            if ctx[r] % 16 == 0:               # the new token opens a page
+                oc, oh = op.alloc(0, spec.n_attn)
+                lc, lh, _ = av.avmp_alloc_auto(g.p, 0, spec.n_attn)
+                assert oc == lc == orc.OK and list(lh) == oh
+                kv[:, r, ctx[r] // 16] = oh
+                g.kv[:, r, ctx[r] // 16] = lh
+        g.sc.ctx = ctx.copy()
+        g.sync_handles()
+        inp = inputs.step_inputs(spec, len(ctx), seed=61, step=step)
+        k_new, v_new = inputs.new_token_kv(spec, len(ctx), seed=61, step=step)
+        ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, ctx, inp["q"], ssm, inp["x"], inp["dt"],
+                                      inp["A"], inp["B"], inp["C"], k_new=k_new, v_new=v_new)
+        o, y = g.step(inp, k_new=k_new, v_new=v_new)
+        _check_outputs(spec, o, y, ref_o, ref_y, "append step %d" % step)
+        ctx += 1
+    for r in range(len(ctx)):
+        for i in range(-(-int(ctx[r]) // 16)):
+            h = int(kv[0, r, i])
+            assert np.array_equal(g.read_unit(h), op.unit_view(h)), "page %d of request %d" % (i, r)
+    _check_states(spec, g, op, ssm, "append loop")
+    g.close()

@@ -284,3 +284,23 @@ def test_single_request_reference_equals_the_whole_batch_oracle():
             o1, y1 = refs[r].step(inp)
             assert np.array_equal(o1, o[:, r]) and np.array_equal(y1, y[:, r])
             assert np.array_equal(refs[r].state(0), p.unit_view(int(ssm[0, r])).view(np.float32).reshape(4, 32, 16))
+
+
+def test_append_then_attend_equals_dense_attention_over_the_longer_sequence():
+    """The append path against the library routine: writing token ctx into its page
+    and attending over ctx + 1 tokens is dense attention over the concatenation."""
+    spec = _spec("bf16", 8, 2, 32)
+    ctx = [1, 15, 16, 31, 47]               # 16 and 32 land on a page boundary: new page needed
+    sc, p, kv, q, logical = _paged_setup(spec, [c + 1 for c in ctx], seed=21)   # pages for ctx+1 exist
+    rng = np.random.default_rng(5)
+    k_new = inputs.elements(rng, (1, len(ctx), 2, 32), 1.0, "bf16")
+    v_new = inputs.elements(rng, (1, len(ctx), 2, 32), 1.0, "bf16")
+    ssm = np.zeros((0, len(ctx)), dtype=np.uint32)
+    z = np.zeros((0,))
+    o, _ = p.decode_step((0,), kv, np.array(ctx, dtype=np.uint32), q[None], ssm, z, z, z, z, z,
+                         k_new=k_new, v_new=v_new)
+    qf = orc.as_f64(q, "bf16")
+    for r, n in enumerate(ctx):
+        K = np.concatenate([logical[r][0][:n], orc.as_f64(k_new[0, r], "bf16")[None]])
+        V = np.concatenate([logical[r][1][:n], orc.as_f64(v_new[0, r], "bf16")[None]])
+        np.testing.assert_allclose(o[0, r], _dense_sdpa(qf[r], K, V, 8, 2), rtol=1e-12, atol=1e-13)
