@@ -237,18 +237,32 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
         if (my_off == ~0ull) count_fault(a.P);
       }
       PageRegs<D> ra, rb;
-      uint64_t off_a = readlane64(my_off, 0);
-      if (off_a != ~0ull)
-        load_page<D>(ra, a.P.arena + off_a + kslab_off, a.P.arena + off_a + vslab_off, lane);
-      for (uint32_t i = 0; i < cnt; i += 2) {
-        const uint64_t off_b = i + 1 < cnt ? readlane64(my_off, i + 1) : ~0ull;
-        if (off_b != ~0ull)
-          load_page<D>(rb, a.P.arena + off_b + kslab_off, a.P.arena + off_b + vslab_off, lane);
-        if (off_a != ~0ull) process(ra, min(16u, n_tok - (base + i) * 16));
-        off_a = i + 2 < cnt ? readlane64(my_off, i + 2) : ~0ull;
-        if (off_a != ~0ull)
-          load_page<D>(ra, a.P.arena + off_a + kslab_off, a.P.arena + off_a + vslab_off, lane);
-        if (off_b != ~0ull) process(rb, min(16u, n_tok - (base + i + 1) * 16));
+      const uint8_t* arena = a.P.arena;
+      if (__ballot(lane < cnt && my_off == ~0ull) == 0) {
+        // every handle of the batch translated: straight-line pipeline
+        uint64_t off_a = readlane64(my_off, 0);
+        load_page<D>(ra, arena + off_a + kslab_off, arena + off_a + vslab_off, lane);
+        for (uint32_t i = 0; i < cnt; i += 2) {
+          const bool has_b = i + 1 < cnt;
+          if (has_b) {
+            const uint64_t off_b = readlane64(my_off, i + 1);
+            load_page<D>(rb, arena + off_b + kslab_off, arena + off_b + vslab_off, lane);
+          }
+          process(ra, min(16u, n_tok - (base + i) * 16));
+          if (i + 2 < cnt) {
+            off_a = readlane64(my_off, i + 2);
+            load_page<D>(ra, arena + off_a + kslab_off, arena + off_a + vslab_off, lane);
+          }
+          if (has_b) process(rb, min(16u, n_tok - (base + i + 1) * 16));
+        }
+      } else {
+        // some handle did not translate: same walk, skipping those pages
+        for (uint32_t i = 0; i < cnt; ++i) {
+          const uint64_t off = readlane64(my_off, i);
+          if (off == ~0ull) continue;
+          load_page<D>(ra, arena + off + kslab_off, arena + off + vslab_off, lane);
+          process(ra, min(16u, n_tok - (base + i) * 16));
+        }
       }
     }
 
