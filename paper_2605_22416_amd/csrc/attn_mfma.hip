@@ -35,12 +35,6 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ uint64_t readlane64(uint64_t v, uint32_t lane) {
-  const uint32_t lo = __builtin_amdgcn_readlane(uint32_t(v), lane);
-  const uint32_t hi = __builtin_amdgcn_readlane(uint32_t(v >> 32), lane);
-  return (uint64_t(hi) << 32) | lo;
-}
-
 template <int D>
 struct PageRegs {
   uint4 k[D / 32];     // K operand tiles of one KV head
@@ -128,6 +122,27 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
   }
 }
 
+// Translation of every KV handle the step will touch, for all attention layers at
+// once: slots[layer][prefix[r] + page] = physical slot (0xFFFFFFFF if the handle does
+// not resolve).  The table cannot change inside a step, so the attention waves read
+// their run's slots as one contiguous load instead of walking handle -> table per
+// page batch, and the table is consulted once per page instead of once per KV head.
+__global__ __launch_bounds__(256) void attn_translate_kernel(DevPools P, const uint32_t* __restrict__ handles,
+                                                             const uint32_t* __restrict__ ctx,
+                                                             const uint32_t* __restrict__ prefix,
+                                                             uint32_t batch, uint32_t max_pages,
+                                                             uint32_t append, uint32_t* __restrict__ slots) {
+  const uint32_t page = blockIdx.x * 256 + threadIdx.x, r = blockIdx.y, la = blockIdx.z;
+  if (page >= pages_of(attended_tokens(ctx, r, append), max_pages)) return;
+  const size_t cap = size_t(batch) * max_pages;
+  const uint32_t h = handles[la * cap + size_t(r) * max_pages + page];
+  const uint64_t off = translate_offset(P, h, 0);
+  uint32_t slot = kDevUnmapped;
+  if (off == ~0ull) count_fault(P);
+  else slot = uint32_t(off / P.unit[0]);
+  slots[la * cap + prefix[r] + page] = slot;
+}
+
 template <int D>
 __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
   constexpr int KK = D / 32;
@@ -140,6 +155,12 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
   const uint64_t item_end = min(uint64_t(total), item + ipw);
   const uint2 start = a.desc[w];
   uint32_t r = start.x, page = start.y;
+  // the run's first 64 slots (for the usual run lengths: all of them), requested before
+  // anything that depends on the context lengths
+  const uint32_t item0 = uint32_t(item);
+  const uint32_t win_n = uint32_t(min(uint64_t(64), item_end - item));
+  const uint32_t my_win = lane < win_n ? a.slots[item0 + lane] : kDevUnmapped;
+  const uint64_t unit_kv = a.P.unit[0];
   const uint32_t G = a.n_kv_heads, Hq = a.n_q_heads, Gq = Hq / G;
   const float scale_log2 = kLog2e / sqrtf(float(D));
   const size_t kslab_off = size_t(g) * D * 32;                        // bytes: [D/8][16][8] bf16
@@ -227,39 +248,41 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
       }
     };
 
-    // Pages are taken 64 at a time: each lane translates one handle, then the
-    // wavefront walks them with one page of loads in flight ahead of the math.
+    // Pages are taken 64 at a time (one slot per lane), then the wavefront walks
+    // them with one page of loads in flight ahead of the math.
     for (uint32_t base = p0; base < p1; base += 64) {
       const uint32_t cnt = min(64u, p1 - base);
-      uint64_t my_off = ~0ull;
-      if (lane < cnt) {
-        my_off = translate_offset(a.P, a.handles[size_t(r) * a.max_pages + base + lane], 0);
-        if (my_off == ~0ull) count_fault(a.P);
-      }
+      const uint32_t it0 = uint32_t(item) + (base - p0);       // flattened index of page `base`
+      uint32_t my_slot;
+      if (it0 - item0 + cnt <= 64)                             // inside the preloaded window
+        my_slot = __shfl(my_win, int((lane + (it0 - item0)) & 63));
+      else
+        my_slot = lane < cnt ? a.slots[it0 + lane] : kDevUnmapped;
       PageRegs<D> ra, rb;
       const uint8_t* arena = a.P.arena;
-      if (__ballot(lane < cnt && my_off == ~0ull) == 0) {
+      if (__ballot(lane < cnt && my_slot == kDevUnmapped) == 0) {
         // every handle of the batch translated: straight-line pipeline
-        uint64_t off_a = readlane64(my_off, 0);
+        uint64_t off_a = uint64_t(__builtin_amdgcn_readlane(my_slot, 0)) * unit_kv;
         load_page<D>(ra, arena + off_a + kslab_off, arena + off_a + vslab_off, lane);
         for (uint32_t i = 0; i < cnt; i += 2) {
           const bool has_b = i + 1 < cnt;
           if (has_b) {
-            const uint64_t off_b = readlane64(my_off, i + 1);
+            const uint64_t off_b = uint64_t(__builtin_amdgcn_readlane(my_slot, i + 1)) * unit_kv;
             load_page<D>(rb, arena + off_b + kslab_off, arena + off_b + vslab_off, lane);
           }
           process(ra, min(16u, n_tok - (base + i) * 16));
           if (i + 2 < cnt) {
-            off_a = readlane64(my_off, i + 2);
+            off_a = uint64_t(__builtin_amdgcn_readlane(my_slot, i + 2)) * unit_kv;
             load_page<D>(ra, arena + off_a + kslab_off, arena + off_a + vslab_off, lane);
           }
           if (has_b) process(rb, min(16u, n_tok - (base + i + 1) * 16));
         }
       } else {
-        // some handle did not translate: same walk, skipping those pages
+        // some handle did not translate (counted by the translation kernel): skip those pages
         for (uint32_t i = 0; i < cnt; ++i) {
-          const uint64_t off = readlane64(my_off, i);
-          if (off == ~0ull) continue;
+          const uint32_t slot = __builtin_amdgcn_readlane(my_slot, i);
+          if (slot == kDevUnmapped) continue;
+          const uint64_t off = uint64_t(slot) * unit_kv;
           load_page<D>(ra, arena + off + kslab_off, arena + off + vslab_off, lane);
           process(ra, min(16u, n_tok - (base + i) * 16));
         }
@@ -396,6 +419,14 @@ hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s) {
                                                   const_cast<uint32_t*>(a.plan),
                                                   const_cast<uint32_t*>(a.prefix),
                                                   const_cast<uint2*>(a.desc));
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_translate(const AttnLaunch& a, const uint32_t* handles_all,
+                                      uint32_t n_attn, uint32_t* slots_all, hipStream_t s) {
+  const dim3 grid((a.max_pages + 255) / 256, a.batch, n_attn);
+  attn_translate_kernel<<<grid, dim3(256), 0, s>>>(a.P, handles_all, a.ctx, a.prefix, a.batch,
+                                                   a.max_pages, a.append, slots_all);
   return hipGetLastError();
 }
 

@@ -443,11 +443,14 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
                                 : size_t(st->batch) * max_chunks * c.n_q_heads;
   const size_t part_floats = part_rows * (size_t(c.head_dim) + 2);
   const size_t plan_words = 4 + (size_t(st->batch) + 2) / 2 * 2 + size_t(runs) * 2;
+  const size_t slot_cap = size_t(st->batch) * st->max_pages;           // per attention layer
+  const size_t slot_words = mfma ? size_t(n_attn) * slot_cap : 0;
   if (n_attn) {
-    rc = ensure_workspace(p, (part_floats + plan_words) * sizeof(float));
+    rc = ensure_workspace(p, (part_floats + plan_words + slot_words) * sizeof(float));
     if (rc != AVMP_OK) return rc;
   }
   uint32_t* plan_base = reinterpret_cast<uint32_t*>(p->ws + part_floats);
+  uint32_t* slots_base = plan_base + plan_words;
   const avmp::DevPools P = p->dev_view();
   uint32_t ia = 0, is = 0;
   bool planned = false;
@@ -460,6 +463,7 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
         a.prefix = plan_base + 4;
         a.desc = reinterpret_cast<const uint2*>(plan_base + 4 + (size_t(st->batch) + 2) / 2 * 2);
         a.runs = runs;
+        a.slots = slots_base + size_t(ia) * slot_cap;
       }
       a.handles = st->kv_handles + size_t(ia) * st->batch * st->max_pages;
       a.ctx = st->ctx;
@@ -486,6 +490,7 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       if (mfma && !planned) {            // context lengths are the same for every layer
         ProfScope scope(p, AVMP_K_TABLE, s);
         HIP_TRY(avmp::launch_attention_plan(a, s));
+        HIP_TRY(avmp::launch_attention_translate(a, st->kv_handles, n_attn, slots_base, s));
         planned = true;
       }
       {

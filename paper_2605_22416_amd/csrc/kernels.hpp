@@ -28,6 +28,7 @@ struct AttnLaunch {
   const uint32_t* plan;      // device [2]: total pages, pages per run
   const uint32_t* prefix;    // device [batch + 1]: page prefix sums
   const uint2* desc;         // device [runs]: each run's starting (request, page)
+  const uint32_t* slots;     // device [total pages]: this layer's pre-translated slots, run order
   uint32_t runs;             // runs (wavefronts) per KV head
 };
 
@@ -51,6 +52,9 @@ bool attention_mfma_supported(uint32_t dtype, uint32_t n_q_heads, uint32_t n_kv_
                               uint32_t head_dim);
 uint32_t attention_runs_per_head(uint32_t n_kv_heads);
 hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s);   // once per decode step
+// once per decode step, after the plan: handles of all attention layers -> slots
+hipError_t launch_attention_translate(const AttnLaunch& a, const uint32_t* handles_all,
+                                      uint32_t n_attn, uint32_t* slots_all, hipStream_t s);
 hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s);
