@@ -143,8 +143,10 @@ __global__ __launch_bounds__(256) void attn_translate_kernel(DevPools P, const u
   slots[la * cap + prefix[r] + page] = slot;
 }
 
+// At least two wavefronts per SIMD for head_dim up to 128 (256 registers each).
 template <int D>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 128 ? 2 : 1)))
+void attn_mfma_kernel(AttnLaunch a) {
   constexpr int KK = D / 32;
   constexpr int NT = D / 16;
   const uint32_t g = blockIdx.x, w = blockIdx.y;
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
     };
 
     // Pages are taken 64 at a time (one slot per lane), then the wavefront walks
-    // them with one page of loads in flight ahead of the math.
+    // them with two pages of loads in flight ahead of the math.
     for (uint32_t base = p0; base < p1; base += 64) {
       const uint32_t cnt = min(64u, p1 - base);
       const uint32_t it0 = uint32_t(item) + (base - p0);       // flattened index of page `base`
@@ -258,24 +260,26 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(AttnLaunch a) {
         my_slot = __shfl(my_win, int((lane + (it0 - item0)) & 63));
       else
         my_slot = lane < cnt ? a.slots[it0 + lane] : kDevUnmapped;
-      PageRegs<D> ra, rb;
+      PageRegs<D> ra, rb, rc;
       const uint8_t* arena = a.P.arena;
       if (__ballot(lane < cnt && my_slot == kDevUnmapped) == 0) {
-        // every handle of the batch translated: straight-line pipeline
-        uint64_t off_a = uint64_t(__builtin_amdgcn_readlane(my_slot, 0)) * unit_kv;
-        load_page<D>(ra, arena + off_a + kslab_off, arena + off_a + vslab_off, lane);
-        for (uint32_t i = 0; i < cnt; i += 2) {
-          const bool has_b = i + 1 < cnt;
-          if (has_b) {
-            const uint64_t off_b = uint64_t(__builtin_amdgcn_readlane(my_slot, i + 1)) * unit_kv;
-            load_page<D>(rb, arena + off_b + kslab_off, arena + off_b + vslab_off, lane);
+        // every handle of the batch translated: straight-line pipeline, three page
+        // buffers, two pages of loads in flight ahead of the math
+        auto fetch = [&](PageRegs<D>& pr, uint32_t i) {
+          if (i < cnt) {
+            const uint64_t off = uint64_t(__builtin_amdgcn_readlane(my_slot, i)) * unit_kv;
+            load_page<D>(pr, arena + off + kslab_off, arena + off + vslab_off, lane);
           }
+        };
+        fetch(ra, 0);
+        fetch(rb, 1);
+        for (uint32_t i = 0; i < cnt; i += 3) {
+          fetch(rc, i + 2);
           process(ra, min(16u, n_tok - (base + i) * 16));
-          if (i + 2 < cnt) {
-            off_a = uint64_t(__builtin_amdgcn_readlane(my_slot, i + 2)) * unit_kv;
-            load_page<D>(ra, arena + off_a + kslab_off, arena + off_a + vslab_off, lane);
-          }
-          if (has_b) process(rb, min(16u, n_tok - (base + i + 1) * 16));
+          fetch(ra, i + 3);
+          if (i + 1 < cnt) process(rb, min(16u, n_tok - (base + i + 1) * 16));
+          fetch(rb, i + 4);
+          if (i + 2 < cnt) process(rc, min(16u, n_tok - (base + i + 2) * 16));
         }
       } else {
         // some handle did not translate (counted by the translation kernel): skip those pages
