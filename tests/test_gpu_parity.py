@@ -401,3 +401,41 @@ def test_decode_loop_with_kv_append_and_page_allocation(dtype):
             assert np.array_equal(g.read_unit(h), op.unit_view(h)), "page %d of request %d" % (i, r)
     _check_states(spec, g, op, ssm, "append loop")
     g.close()
+
+
+@pytest.mark.parametrize("dtype,Hq,G,D,H,P,N", [
+    ("bf16", 16, 1, 64, 3, 24, 16),     # matrix-core kernel, head_dim 64, query group of 16; small SSM tiles
+    ("bf16", 8, 8, 256, 2, 40, 256),    # matrix-core kernel, head_dim 256, no grouping; dstate 256 (64 lanes per row)
+    ("bf16", 6, 2, 128, 5, 64, 64),     # query group of 3 (partly filled tile); 1024-thread SSM kernel, runtime geometry
+    ("bf16", 4, 2, 32, 2, 8, 4),        # head_dim 32: vector-ALU attention kernel on bf16; dstate 4
+    ("bf16", 32, 1, 128, 2, 128, 128),  # query group of 32 > 16: vector-ALU kernel; headdim 128 (two passes)
+    ("f32", 6, 3, 48, 3, 20, 32),       # fp32, odd head_dim
+])
+def test_other_head_shapes(dtype, Hq, G, D, H, P, N):
+    """Every kernel instantiation and dispatch branch, on shapes other than the
+    two workload shapes, with ragged contexts and NaN poison."""
+    spec = inputs.ModelSpec("shape", dtype, 16, Hq, G, D, H, P, N,
+                            (inputs.SSM, inputs.ATTN, inputs.ATTN, inputs.SSM), True)
+    ctx = [0, 1, 16, 47, 130, 700, 1500]
+    sc = inputs.make_scenario(spec, "uniform_short", len(ctx), seed=71, ctx=ctx)
+    op, g, kv, ssm = _both(sc, poison=True)
+    for step in range(2):
+        inp = inputs.step_inputs(spec, len(ctx), seed=71, step=step)
+        ref_o, ref_y = _oracle_step(op, sc, kv, ssm, inp)
+        o, y = g.step(inp)
+        _check_outputs(spec, o, y, ref_o, ref_y, "shape %s step %d" % ((dtype, Hq, G, D, H, P, N), step))
+    _check_states(spec, g, op, ssm, "shapes")
+    g.close()
+
+
+def test_one_long_request_spreads_over_all_runs():
+    """A single 40000-token request: its pages are cut into 256 runs per KV head,
+    so the merge combines more than 64 partial results per row."""
+    spec = inputs.ModelSpec("long1", "bf16", 16, 8, 2, 128, 2, 8, 16, (inputs.ATTN, inputs.SSM), True)
+    sc = inputs.make_scenario(spec, "uniform_short", 1, seed=72, ctx=[40000])
+    op, g, kv, ssm = _both(sc)
+    inp = inputs.step_inputs(spec, 1, seed=72)
+    ref_o, ref_y = _oracle_step(op, sc, kv, ssm, inp)
+    o, y = g.step(inp)
+    _check_outputs(spec, o, y, ref_o, ref_y, "one long request")
+    g.close()
