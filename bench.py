@@ -28,15 +28,19 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the SSM kernel at this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs scaled by the same counters' readings for the plain migration copy (summary under
 # profiles/).  Valid only for the kernel source it was measured on: reported as null otherwise.
-SSM_TRAFFIC = {"source_sha256_16": "1f97b82634f4b519", "batch": 64, "bytes_per_launch": 527263 * 1024}
+SSM_TRAFFIC = {"source_sha256_16": "4bf331be2c9d3a94", "batch": 64, "bytes_per_launch": 527271 * 1024}
 
 
 def ssm_traffic(batch):
     import hashlib
     src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "ssm_update.hip")
     try:
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
-    except OSError:
+        text = open(src).read()
+        # the fp32-state kernel only: from its signature to the start of the bf16-state section
+        i = text.index("void ssm_update_kernel(SsmLaunch a) {")
+        j = text.index("// Same update with the state stored as bf16")
+        digest = hashlib.sha256(text[i:j].encode()).hexdigest()[:16]
+    except (OSError, ValueError):
         return None
     if digest != SSM_TRAFFIC["source_sha256_16"] or batch != SSM_TRAFFIC["batch"]:
         return None
@@ -57,7 +61,7 @@ def ssm_bytes(spec):
     x in, y out, B, C, dt and the handle + table entry."""
     e = spec.elem_bytes
     H, P, N = spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate
-    return 2 * H * P * N * 4 + H * P * e + H * P * 4 + 2 * N * e + H * 4 + 8
+    return 2 * H * P * N * spec.state_bytes + H * P * e + H * P * 4 + 2 * N * e + H * 4 + 8
 
 
 def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=64):
@@ -109,6 +113,8 @@ def main():
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="uniform_short")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--state-dtype", choices=("f32", "bf16"), default="f32",
+                    help="storage type of the SSM state blocks (f32 is the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
@@ -130,6 +136,8 @@ def main():
         sys.exit(1)
 
     spec = inputs.JAMBA_MINI
+    if args.state_dtype != "f32":
+        spec = inputs.with_state_dtype(spec, args.state_dtype)
     wl = WORKLOADS[args.workload]
     args.batch = wl["batch"] if args.batch is None else args.batch
     args.seed = wl["seed"] if args.seed is None else args.seed
@@ -241,7 +249,8 @@ def main():
         a = kernels["ssm"]["GBps"]
         roofline = {"kernel": "ssm_update_kernel", "bound": "hbm", "achieved": a,
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                    "traffic": ssm_traffic(sc.batch), "bytes_per_launch": ssm_layer_bytes,
+                    "traffic": ssm_traffic(sc.batch) if args.state_dtype == "f32" else None,
+                    "bytes_per_launch": ssm_layer_bytes,
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
 
     # ---- migration sweep (outside the timed region): pages/s of capacity moved ----------
@@ -283,6 +292,7 @@ def main():
                                "freed and re-allocated) + decode + %d-page migration round trip"
                                % (wl["text"], sc.batch, churn_kv, churn_ssm, mig_pages),
                    "name": args.workload, "batch": sc.batch, "seed": args.seed,
+                   "ssm_state_dtype": args.state_dtype,
                    "arena_GB": sc.arena_bytes / 1e9},
         "ms_per_step_with_kernel_events": (wall_ev / args.steps * 1e3) if wall_ev else None,
         "algorithmic_bytes_per_step": step_bytes,

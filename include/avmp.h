@@ -37,7 +37,8 @@
  * With T = 16 tokens, G = KV heads, D = head_dim, x = 16 / element_bytes:
  *    K element (g, t, d) at element index ((g*(D/x) + d/x)*T + t)*x + d%x
  *    V element (g, t, d) at element index G*T*D + (g*D + d)*T + t
- * An SSM block is fp32 [ssm_heads][ssm_headdim][ssm_dstate], row-major.
+ * An SSM block is [ssm_heads][ssm_headdim][ssm_dstate], row-major, fp32 or bf16
+ * (ssm_state_dtype).
  */
 #ifndef AVMP_H
 #define AVMP_H
@@ -77,6 +78,9 @@ typedef struct avmp_config {
   uint32_t ssm_heads;              /* H */
   uint32_t ssm_headdim;            /* P */
   uint32_t ssm_dstate;             /* N: power of two, 4..256 */
+  uint32_t ssm_state_dtype;        /* AVMP_F32 (default, 0) or AVMP_BF16: storage type of the SSM
+                                      state in its block (the paper's bytes_per_element).
+                                      Arithmetic is fp32 either way; bf16 storage needs N >= 8 */
   uint32_t kv_capacity;            /* initial KV pool capacity in pages */
   uint32_t ssm_capacity;           /* initial SSM pool capacity in blocks */
   uint32_t max_vid[2];             /* virtual ids per pool; 0 = as many as slots could ever exist */
@@ -144,7 +148,7 @@ typedef struct avmp_step {
 
 /* Size arithmetic of Method, "Asymmetric Virtual Page Table": KV page =
  * attention_page_tokens x per_token_bytes (K and V of one attention layer, all
- * KV heads), SSM block = state_dim x 4 bytes; both rounded up to 16.
+ * KV heads), SSM block = state_dim x bytes_per_element (4 or 2); both rounded up to 16.
  * Host only.  AVMP_ERR_INVALID_ARG on unsupported shapes. */
 int avmp_geometry(const avmp_config_t* cfg, size_t arena_bytes, avmp_geometry_t* out);
 
@@ -185,7 +189,8 @@ int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, vo
  * every layer of `step`, enqueued on `stream`.  Attention per (request r, query
  * head j, g = j / (n_q_heads/n_kv_heads)): o = softmax_t(q.K_t[g]/sqrt(D)) . V[g]
  * over the ctx[r] resident tokens; SSM per (r, h, p, n): a = exp(dt*A),
- * S <- a*S + dt*x*B[n] in place, y = sum_n S*C[n] with the updated S. */
+ * S <- a*S + dt*x*B[n] in place, y = sum_n S*C[n] with the updated S (before it is
+ * rounded to a bf16 block, when the state is stored as bf16). */
 int avmp_decode_step(avmp_pools_t* pools, const avmp_step_t* step, void* stream);
 
 /* Rebalancing policy of Method, "Dynamic Pool Rebalancing" and Fig. 2.  A

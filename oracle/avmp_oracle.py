@@ -90,10 +90,15 @@ class Shape:
     ssm_heads: int        # H
     ssm_headdim: int      # P
     ssm_dstate: int       # N
+    state_dtype: str = "f32"   # storage type of the SSM state (bytes_per_element of the block)
 
     @property
     def elem_bytes(self) -> int:
         return ELEM_BYTES[self.dtype]
+
+    @property
+    def state_bytes(self) -> int:
+        return ELEM_BYTES[self.state_dtype]
 
     @property
     def per_token_bytes(self) -> int:
@@ -107,7 +112,7 @@ class Shape:
         if pool == POOL_KV:
             raw = self.page_tokens * self.per_token_bytes
         else:
-            raw = self.state_dim * 4          # state is carried in fp32
+            raw = self.state_dim * self.state_bytes    # state_dim x bytes_per_element
         return round_up(raw, PAGE_ALIGN)
 
 
@@ -117,6 +122,18 @@ def decode_elements(raw: np.ndarray, dtype: str) -> np.ndarray:
         return raw.view(np.float32).astype(np.float64)
     u = raw.view(np.uint16).astype(np.uint32) << 16
     return u.view(np.float32).astype(np.float64)
+
+
+def round_to_bf16_bits(v: np.ndarray) -> np.ndarray:
+    """float64 -> nearest bf16 (8 significant bits, ties to even), as uint16 bit patterns.
+    Written from the format's definition: v = m * 2^e with 0.5 <= |m| < 1 is kept to
+    a multiple of 2^(e-8) (8 significant bits), and never finer than 2^-133, the
+    smallest subnormal."""
+    v = np.asarray(v, dtype=np.float64)
+    m, e = np.frexp(v)
+    qe = np.maximum(e - 8, -133)
+    q = np.ldexp(np.rint(np.ldexp(v, -qe)), qe)           # np.rint rounds halves to even
+    return (q.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)   # exact: q is representable
 
 
 def as_f64(a: np.ndarray, dtype: str) -> np.ndarray:
@@ -177,6 +194,8 @@ class Pools:
         self.slot_of = [np.full(self.max_vid[p], UNMAPPED, dtype=np.int64) for p in range(N_POOLS)]
         self.vid_of = [np.full(self.max_slots[p], UNMAPPED, dtype=np.int64) for p in range(N_POOLS)]
         self.arena = np.zeros(self.usable, dtype=np.uint8) if with_data else None
+        self.unrounded_state = {}      # handle -> float64 state of its last update, before storage
+        self.update_scale = {}         # handle -> |a*S| + |dt*x*B| of that update (rounding-noise scale)
         # counters (the 64-bit logical operation counter of the paper + outcome counters)
         self.ops = 0
         self.capacity_errors = 0
@@ -319,6 +338,13 @@ class Pools:
             "bytes_wasted": self.bytes_wasted,
         }
 
+    def state_values(self, h: int) -> np.ndarray:
+        """The SSM block behind handle h as float64 [H][P][N]."""
+        sh = self.shape
+        n = sh.state_dim * sh.state_bytes
+        return decode_elements(self.unit_view(h)[:n], sh.state_dtype).reshape(
+            sh.ssm_heads, sh.ssm_headdim, sh.ssm_dstate)
+
     # ---- raw unit access by handle ------------------------------------------
     def unit_view(self, h: int) -> np.ndarray:
         r = self.resolve(h)
@@ -408,8 +434,8 @@ class Pools:
              a = exp(dt[r,h] * A[h])
              S[h,p,n] <- a * S[h,p,n] + dt[r,h] * x[r,h,p] * B[r,n]
              y[r,h,p] = sum_n S[h,p,n] * C[r,n]          (with the updated S)
-        The block is updated in place (stored rounded once to fp32); y uses the
-        updated value before that rounding.  x: [batch][H][P], B, C: [batch][N]
+        The block is updated in place (stored rounded once to the state dtype);
+        y uses the updated value before that rounding.  x: [batch][H][P], B, C: [batch][N]
         in the element dtype; dt: [batch][H] fp32; A: [H] fp32.  Returns float64."""
         sh = self.shape
         H, P, N = sh.ssm_heads, sh.ssm_headdim, sh.ssm_dstate
@@ -421,12 +447,19 @@ class Pools:
             res = self.resolve(int(handles[r]))
             if res is None or res[0] != POOL_SSM:
                 raise KeyError("request %d: not a live SSM handle" % r)
-            blk = self.arena[res[2]: res[2] + H * P * N * 4].view(np.float32).reshape(H, P, N)
-            S = blk.astype(np.float64)
+            raw = self.arena[res[2]: res[2] + H * P * N * sh.state_bytes]
+            S = decode_elements(raw, sh.state_dtype).reshape(H, P, N)
             a = np.exp(dtf[r] * Af)                                   # [H]
-            S = a[:, None, None] * S + (dtf[r][:, None] * xf[r])[:, :, None] * Bf[r][None, None, :]
+            decayed = a[:, None, None] * S
+            driven = (dtf[r][:, None] * xf[r])[:, :, None] * Bf[r][None, None, :]
+            self.update_scale[int(handles[r])] = np.abs(decayed) + np.abs(driven)
+            S = decayed + driven
             y[r] = (S * Cf[r][None, None, :]).sum(axis=2)
-            blk[...] = S.astype(np.float32)
+            self.unrounded_state[int(handles[r])] = S      # for tests of the storage rounding
+            if sh.state_dtype == "f32":
+                raw.view(np.float32)[:] = S.astype(np.float32).reshape(-1)
+            else:
+                raw.view(np.uint16)[:] = round_to_bf16_bits(S).reshape(-1)
         return y
 
     # ---- one hybrid decode step ------------------------------------------------

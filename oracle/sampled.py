@@ -16,7 +16,7 @@ from paper_2605_22416_amd import inputs
 
 def oracle_shape(spec) -> orc.Shape:
     return orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate)
+                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype)
 
 
 class RequestReference:
@@ -55,6 +55,4 @@ class RequestReference:
         return o[:, 0], y[:, 0]
 
     def state(self, layer: int) -> np.ndarray:
-        sp = self.spec
-        return self.pools.unit_view(int(self.ssm[layer, 0])).view(np.float32).reshape(
-            sp.ssm_heads, sp.ssm_headdim, sp.ssm_dstate)
+        return self.pools.state_values(int(self.ssm[layer, 0]))

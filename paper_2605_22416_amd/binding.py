@@ -62,7 +62,7 @@ class avmp_config_t(C.Structure):
     _fields_ = [("dtype", C.c_uint32), ("attention_page_tokens", C.c_uint32),
                 ("n_q_heads", C.c_uint32), ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
                 ("ssm_heads", C.c_uint32), ("ssm_headdim", C.c_uint32), ("ssm_dstate", C.c_uint32),
-                ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
+                ("ssm_state_dtype", C.c_uint32), ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
                 ("max_vid", C.c_uint32 * 2), ("slot_rank", C.POINTER(C.c_uint32) * 2)]
 
 
@@ -165,13 +165,14 @@ def _stream(s) -> Optional[int]:
 def make_config(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, ssm_heads: int,
                 ssm_headdim: int, ssm_dstate: int, kv_capacity: int, ssm_capacity: int,
                 slot_rank: Optional[Sequence[Optional[np.ndarray]]] = None,
-                max_vid: Sequence[int] = (0, 0), page_tokens: int = 16):
+                max_vid: Sequence[int] = (0, 0), page_tokens: int = 16, state_dtype: str = "f32"):
     """Returns (avmp_config_t, keepalive): keepalive holds the rank arrays the struct points to."""
     cfg = avmp_config_t()
     cfg.dtype = AVMP_F32 if dtype == "f32" else AVMP_BF16
     cfg.attention_page_tokens = page_tokens
     cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_q_heads, n_kv_heads, head_dim
     cfg.ssm_heads, cfg.ssm_headdim, cfg.ssm_dstate = ssm_heads, ssm_headdim, ssm_dstate
+    cfg.ssm_state_dtype = AVMP_F32 if state_dtype == "f32" else AVMP_BF16
     cfg.kv_capacity, cfg.ssm_capacity = kv_capacity, ssm_capacity
     cfg.max_vid[0], cfg.max_vid[1] = max_vid
     keep = []

@@ -148,6 +148,9 @@ bool shape_from_config(const avmp_config_t* c, avmp::ShapeArgs* s) {
   if (c->head_dim == 0 || c->head_dim % x != 0 || c->head_dim > 256) return false;
   const uint32_t n = c->ssm_dstate;
   if (n < 4 || n > 256 || (n & (n - 1)) != 0) return false;
+  if (c->ssm_state_dtype != AVMP_F32 && c->ssm_state_dtype != AVMP_BF16) return false;
+  s->state_bytes = c->ssm_state_dtype == AVMP_F32 ? 4 : 2;
+  if (s->state_bytes == 2 && n < 8) return false;      // a lane moves 16 bytes = 8 bf16 of a row
   if (c->ssm_heads == 0 || c->ssm_headdim == 0) return false;
   if (c->ssm_heads > 65535 || c->n_q_heads > 65535) return false;
   s->page_tokens = c->attention_page_tokens;
@@ -518,6 +521,7 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.headdim = c.ssm_headdim;
       a.dstate = c.ssm_dstate;
       a.dtype = c.dtype;
+      a.state_dtype = c.ssm_state_dtype;
       {
         ProfScope scope(p, AVMP_K_SSM, s);
         HIP_TRY(avmp::launch_ssm(a, s));

@@ -42,7 +42,8 @@ struct SsmLaunch {
   const void* C;             // device [batch][N]
   float* y;                  // device [batch][H][P]
   uint32_t batch, heads, headdim, dstate;
-  uint32_t dtype;
+  uint32_t dtype;            // x, B, C element type: 0 f32, 1 bf16
+  uint32_t state_dtype;      // storage type of the state block: 0 f32, 1 bf16
 };
 
 hipError_t launch_kv_append(const AttnLaunch& a, hipStream_t s);

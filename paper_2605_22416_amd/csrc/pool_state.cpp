@@ -59,13 +59,13 @@ static uint64_t round_up(uint64_t v, uint64_t m) { return (v + m - 1) / m * m; }
 
 bool compute_geometry(const ShapeArgs& s, uint64_t arena_bytes, Geometry* g) {
   if (s.elem_bytes == 0 || s.page_tokens == 0 || s.n_kv_heads == 0 || s.head_dim == 0 ||
-      s.ssm_heads == 0 || s.ssm_headdim == 0 || s.ssm_dstate == 0)
+      s.ssm_heads == 0 || s.ssm_headdim == 0 || s.ssm_dstate == 0 || s.state_bytes == 0)
     return false;
   // KV page = attention_page_tokens x per_token_bytes; per_token_bytes = K and V
-  // of one layer for all KV heads.  SSM block = state_dim x 4 (fp32 state).
+  // of one layer for all KV heads.  SSM block = state_dim x bytes_per_element.
   uint64_t per_token = 2ull * s.n_kv_heads * s.head_dim * s.elem_bytes;
   g->unit[0] = round_up(uint64_t(s.page_tokens) * per_token, 16);
-  g->unit[1] = round_up(uint64_t(s.ssm_heads) * s.ssm_headdim * s.ssm_dstate * 4ull, 16);
+  g->unit[1] = round_up(uint64_t(s.ssm_heads) * s.ssm_headdim * s.ssm_dstate * s.state_bytes, 16);
   g->usable = arena_bytes / 128 * 128;
   for (int p = 0; p < kPools; ++p) {
     uint64_t m = g->usable / g->unit[p];

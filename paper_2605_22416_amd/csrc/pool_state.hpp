@@ -54,7 +54,7 @@ struct Counters {
 
 struct ShapeArgs {
   uint32_t elem_bytes, page_tokens, n_q_heads, n_kv_heads, head_dim, ssm_heads, ssm_headdim,
-      ssm_dstate;
+      ssm_dstate, state_bytes;
 };
 
 // Returns false if the shape is unusable (zero sizes, more than 2^30 slots).

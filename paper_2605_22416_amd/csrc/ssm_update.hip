@@ -103,6 +103,103 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Same update with the state stored as bf16 (half the state traffic).  A lane
+// moves 16 bytes = 8 state elements, so a row's N values sit in N/8 adjacent
+// lanes.  Arithmetic is fp32: the stored bf16 is widened exactly, updated,
+// reduced into y un-rounded, then rounded to nearest even for the store.
+// ---------------------------------------------------------------------------
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+
+template <typename E>
+__device__ __forceinline__ void load8(const E* p, float (&v)[8]);
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float (&v)[8]) {
+  const uint4 u = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    v[2 * j] = __uint_as_float(w[j] << 16);
+    v[2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+  }
+}
+
+__device__ __forceinline__ uint32_t bf16_round_bits(float f) {   // round to nearest, ties to even
+  const uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// HPB heads share one workgroup (THREADS / HPB threads each), so that a workgroup
+// still moves a 32 KiB burst at the Mamba-2 shape (two heads: 51.5 us per layer at
+// batch 64, against 55.7 us with one head and 54.4 us with four).
+template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1>
+__global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch a) {
+  constexpr uint32_t TPH = THREADS / HPB;            // threads per head
+  const uint32_t h = blockIdx.x * HPB + threadIdx.x / TPH, r = blockIdx.y, tid = threadIdx.x % TPH;
+  const uint32_t H = a.heads, Pd = a.headdim;
+  const uint32_t N = NS ? uint32_t(NS) : a.dstate;
+  const uint64_t off = translate_offset(a.P, a.handles[r], 1);
+  float* yrow = a.y + (size_t(r) * H + h) * Pd;
+  if (off == ~0ull) {
+    if (tid == 0) count_fault(a.P);
+    for (uint32_t p = tid; p < Pd; p += TPH) yrow[p] = 0.f;
+    return;
+  }
+  const uint32_t lpr = N / 8;                  // lanes per row (power of two, <= 32)
+  const uint32_t col = tid & (lpr - 1);
+  const uint32_t row0 = tid / lpr;
+  const uint32_t rpi = TPH / lpr;
+  const float dt = a.dt[size_t(r) * H + h];
+  const float decay = expf(dt * a.A[h]);
+  float Bv[8], Cv[8];
+  load8<E>(static_cast<const E*>(a.B) + size_t(r) * N + 8 * col, Bv);
+  load8<E>(static_cast<const E*>(a.C) + size_t(r) * N + 8 * col, Cv);
+  const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
+  uint16_t* S = reinterpret_cast<uint16_t*>(a.P.arena + off) + size_t(h) * Pd * N + 8 * col;
+
+  for (uint32_t pbase = row0; pbase < Pd; pbase += rpi * ROWS) {
+    u32x4s raw[ROWS];
+    float xs[ROWS];
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+      const uint32_t p = pbase + k * rpi;
+      if (EXACT || p < Pd) {
+        raw[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4s*>(S + size_t(p) * N));
+        xs[k] = load_elem<E>(xrow + p);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+      const uint32_t p = pbase + k * rpi;
+      float part = 0.f;
+      if (EXACT || p < Pd) {
+        const float dtx = dt * xs[k];
+        const uint32_t w[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+        uint32_t out[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float lo = decay * __uint_as_float(w[j] << 16) + dtx * Bv[2 * j];
+          const float hi = decay * __uint_as_float(w[j] & 0xFFFF0000u) + dtx * Bv[2 * j + 1];
+          part += lo * Cv[2 * j] + hi * Cv[2 * j + 1];
+          out[j] = bf16_round_bits(lo) | (bf16_round_bits(hi) << 16);
+        }
+        const u32x4s packed = {out[0], out[1], out[2], out[3]};
+        __builtin_nontemporal_store(packed, reinterpret_cast<u32x4s*>(S + size_t(p) * N));
+      }
+#pragma unroll
+      for (uint32_t o = 16; o; o >>= 1)
+        if (o < lpr) part += __shfl_xor(part, int(o));
+      if ((EXACT || p < Pd) && col == 0) yrow[p] = part;
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
@@ -113,6 +210,23 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   // the Mamba-2 shape (dstate 128, headdim a multiple of 64) gets a kernel with
   // compile-time row geometry and no bounds tests
   const bool exact128 = a.dstate == 128 && a.headdim % 64 == 0;
+  if (a.state_dtype == 1) {
+    const bool big16 = uint64_t(a.headdim) * (a.dstate / 8) >= 1024;
+    if (a.dtype == 0) {
+      if (exact128 && a.heads % 2 == 0)
+        ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      else if (exact128) ssm_update_bf16state_kernel<float, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
+      else if (big16) ssm_update_bf16state_kernel<float, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
+      else ssm_update_bf16state_kernel<float, 256, 2, 0, false><<<grid, dim3(256), 0, s>>>(a);
+    } else {
+      if (exact128 && a.heads % 2 == 0)
+        ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      else if (exact128) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
+      else if (big16) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
+      else ssm_update_bf16state_kernel<uint16_t, 256, 2, 0, false><<<grid, dim3(256), 0, s>>>(a);
+    }
+    return hipGetLastError();
+  }
   if (a.dtype == 0) {
     if (exact128) ssm_update_kernel<float, 1024, 2, 128, true><<<grid, dim3(1024), 0, s>>>(a);
     else if (big) ssm_update_kernel<float, 1024, 2, 0, false><<<grid, dim3(1024), 0, s>>>(a);

@@ -14,7 +14,7 @@ from __future__ import annotations
 
 import math
 from concurrent.futures import ThreadPoolExecutor
-from dataclasses import dataclass
+from dataclasses import dataclass, replace
 from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
@@ -36,6 +36,11 @@ class ModelSpec:
     ssm_dstate: int
     layer_kinds: Tuple[int, ...]    # model order; 0 = attention, 1 = SSM
     scale_inputs: bool              # q, K, V, x drawn N(0,1) then scaled by 1/sqrt(head dim)
+    state_dtype: str = "f32"        # storage type of the SSM state in its block: "f32" or "bf16"
+
+    @property
+    def state_bytes(self) -> int:
+        return 4 if self.state_dtype == "f32" else 2
 
     @property
     def elem_bytes(self) -> int:
@@ -55,7 +60,7 @@ class ModelSpec:
 
     @property
     def ssm_block_bytes(self) -> int:
-        return self.ssm_heads * self.ssm_headdim * self.ssm_dstate * 4
+        return self.ssm_heads * self.ssm_headdim * self.ssm_dstate * self.state_bytes
 
 
 # one attention + one SSM layer, fp32, 4 query / 2 KV heads x 64, SSM 4 x 32 x 16
@@ -70,9 +75,12 @@ JAMBA_MINI = ModelSpec("jamba_mini_like", "bf16", 16, 32, 8, 128, 128, 64, 128,
 def scaled_down(spec: ModelSpec, n_blocks: int = 1, name: Optional[str] = None) -> ModelSpec:
     """Same head shapes, fewer layers (n_blocks repeats of 1 attention + 7 SSM)."""
     kinds = tuple(ATTN if i % 8 == 4 else SSM for i in range(8 * n_blocks))
-    return ModelSpec(name or spec.name + "_%dblk" % n_blocks, spec.dtype, spec.page_tokens,
-                     spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.ssm_heads,
-                     spec.ssm_headdim, spec.ssm_dstate, kinds, spec.scale_inputs)
+    return replace(spec, name=name or spec.name + "_%dblk" % n_blocks, layer_kinds=kinds)
+
+
+def with_state_dtype(spec: ModelSpec, state_dtype: str) -> ModelSpec:
+    """Same model with the SSM state stored as "f32" or "bf16" in its block."""
+    return replace(spec, name=spec.name + "_state_" + state_dtype, state_dtype=state_dtype)
 
 
 # ----------------------------------------------------------------------------
@@ -214,15 +222,15 @@ def new_token_kv(spec: ModelSpec, batch: int, seed: int, step: int = 0,
 def unit_content(spec: ModelSpec, seed: int, pool: int, layer: int, request: int,
                  index: int = 0, scale_inputs: Optional[bool] = None) -> np.ndarray:
     """Bytes of one KV page (K and V values for page `index` of `request` in
-    attention layer ordinal `layer`) or of one SSM state block (fp32 N(0,1))."""
+    attention layer ordinal `layer`) or of one SSM state block (N(0,1) in the state dtype)."""
     rng = np.random.default_rng([seed, 3, pool, layer, request, index])
     if pool == POOL_KV:
         sc = spec.scale_inputs if scale_inputs is None else scale_inputs
         s = 1.0 / math.sqrt(spec.head_dim) if sc else 1.0
         n = spec.kv_page_bytes // spec.elem_bytes
         return elements(rng, n, s, spec.dtype).view(np.uint8)
-    n = spec.ssm_block_bytes // 4
-    return rng.standard_normal(n, dtype=np.float32).view(np.uint8)
+    n = spec.ssm_block_bytes // spec.state_bytes
+    return elements(rng, n, 1.0, spec.state_dtype).view(np.uint8)
 
 
 def fill_units(spec: ModelSpec, seed: int, jobs: Sequence[Tuple[int, int, int, int]],

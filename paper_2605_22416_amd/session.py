@@ -63,7 +63,8 @@ class DeviceSession:
             self.arena.fill_(fill_byte)
         cfg, self._keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                                          spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate,
-                                         sc.kv_capacity, sc.ssm_capacity, slot_rank=sc.slot_rank)
+                                         sc.kv_capacity, sc.ssm_capacity, slot_rank=sc.slot_rank,
+                                         state_dtype=spec.state_dtype)
         rc, self.p = av.avmp_pools_create(cfg, self.arena, sc.arena_bytes)
         if rc != av.AVMP_OK:
             raise RuntimeError("avmp_pools_create: " + av.avmp_last_error())
@@ -161,11 +162,16 @@ class DeviceSession:
         return o.cpu().numpy(), y.cpu().numpy()
 
     def states(self, layer: int, requests=None) -> np.ndarray:
-        """SSM blocks of one SSM layer read back by handle: [len(requests)][H][P][N] fp32."""
+        """SSM blocks of one SSM layer read back by handle: [len(requests)][H][P][N] as
+        float32 (bf16 storage is widened; every bf16 value is a float32)."""
         spec = self.sc.spec
         rs = range(self.sc.batch) if requests is None else requests
-        return np.stack([self.read_unit(int(self.ssm[layer, r])).view(np.float32).reshape(
-            spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate) for r in rs])
+        out = []
+        for r in rs:
+            raw = self.read_unit(int(self.ssm[layer, r]))
+            vals = raw.view(np.float32) if spec.state_dtype == "f32" else inputs.bf16_bits_to_f32(raw.view(np.uint16))
+            out.append(vals.reshape(spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate))
+        return np.stack(out)
 
     def translate(self, handles: np.ndarray) -> np.ndarray:
         h = to_dev(np.ascontiguousarray(handles, dtype=np.uint32).reshape(-1))

@@ -25,5 +25,4 @@ class GpuPools(DeviceSession):
 
 
 def oracle_states(op, ssm_handles, spec) -> np.ndarray:
-    return np.stack([op.unit_view(int(h)).view(np.float32).reshape(
-        spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate).copy() for h in ssm_handles])
+    return np.stack([op.state_values(int(h)) for h in ssm_handles])

@@ -17,7 +17,7 @@ using namespace avmp;
 int main(int argc, char** argv) {
   const unsigned seed = argc > 1 ? unsigned(std::atoi(argv[1])) : 1u;
   std::mt19937 rng(seed);
-  ShapeArgs sh{4, 16, 4, 2, 64, 4, 32, 16};
+  ShapeArgs sh{4, 16, 4, 2, 64, 4, 32, 16, 4};
   Geometry g{};
   const uint64_t arena = 37 * 16384 + 11 * 8192 + 640;
   REQUIRE(compute_geometry(sh, arena, &g));

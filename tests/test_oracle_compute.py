@@ -304,3 +304,45 @@ def test_append_then_attend_equals_dense_attention_over_the_longer_sequence():
         K = np.concatenate([logical[r][0][:n], orc.as_f64(k_new[0, r], "bf16")[None]])
         V = np.concatenate([logical[r][1][:n], orc.as_f64(v_new[0, r], "bf16")[None]])
         np.testing.assert_allclose(o[0, r], _dense_sdpa(qf[r], K, V, 8, 2), rtol=1e-12, atol=1e-13)
+
+
+def test_bf16_rounding_equals_the_library_conversion():
+    """round_to_bf16_bits against torch's float -> bfloat16 (round to nearest even),
+    on random values, exact ties and values one float32 ulp either side of a tie."""
+    rng = np.random.default_rng(2)
+    v = np.concatenate([rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000)),
+                        [0.0, -0.0, 1.0, -1.0, 3.0e-30, 6.5e30]]).astype(np.float32)
+    base = (v.view(np.uint32) & np.uint32(0xFFFF0000))
+    ties = (base | np.uint32(0x8000)).view(np.float32)            # exactly halfway between two bf16 values
+    near = np.concatenate([(base | np.uint32(0x8001)).view(np.float32), (base | np.uint32(0x7FFF)).view(np.float32)])
+    allv = np.concatenate([v, ties, near])
+    want = torch.from_numpy(allv).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = orc.round_to_bf16_bits(allv.astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_ssm_step_with_bf16_state_storage():
+    """State stored as bf16: y still comes from the un-rounded updated state, the
+    block holds its nearest bf16 (B = 0: exactly bf16(a * s), checked through torch)."""
+    spec = inputs.with_state_dtype(_spec("bf16", 1, 1, 16, H=2, P=3, N=8), "bf16")
+    assert spec.ssm_block_bytes == 2 * 3 * 8 * 2
+    sc, p, ssm = _ssm_setup(spec, 1, seed=13)
+    h = int(ssm[0, 0])
+    assert p.unit[1] == spec.ssm_block_bytes
+    p.unit_view(h)[:] = inputs.unit_content(spec, 13, 1, 0, 0, 0)
+    S0 = p.state_values(h).copy()
+    inp = inputs.step_inputs(spec, 1, seed=43)
+    x, dt, A, B, C = (inp[k][0] for k in ("x", "dt", "A", "B", "C"))
+    y = p.ssm_step(ssm[0], x, dt, A, np.zeros_like(B), C)
+    a = np.exp(dt[0].astype(np.float64) * A.astype(np.float64))
+    exact = a[:, None, None] * S0
+    want = torch.from_numpy(exact).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(p.state_values(h), want)
+    Cf = orc.as_f64(C, "bf16")
+    np.testing.assert_allclose(y[0], (exact * Cf[0][None, None, :]).sum(axis=2), rtol=1e-13)
+    # with B != 0 the stored value is within half a bf16 ulp of the exact update
+    S1 = p.state_values(h).copy()
+    p.ssm_step(ssm[0], x, dt, A, B, C)
+    xf, Bf = orc.as_f64(x, "bf16"), orc.as_f64(B, "bf16")
+    exact = a[:, None, None] * S1 + (dt[0].astype(np.float64)[:, None] * xf[0])[:, :, None] * Bf[0][None, None, :]
+    assert (np.abs(p.state_values(h) - exact) <= np.abs(exact) * 2.0 ** -8).all()
