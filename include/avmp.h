@@ -21,6 +21,13 @@
  *    avmp_decode_step, avmp_migrate, avmp_flush and avmp_translate are
  *    asynchronous on it.  All device work of one pools object must be issued
  *    on one stream or be ordered by the caller.
+ *  - AVMP_ERR_DEVICE from avmp_migrate, avmp_alloc_auto or avmp_decode_step means a
+ *    HIP call failed after host metadata may already have changed: the pools
+ *    object must then be destroyed.  Every other error is a clean no-op.
+ *  - avmp_decode_step grows its work buffer on first use and when a larger
+ *    batch or handle row arrives (a device synchronisation and an allocation);
+ *    with that done and nothing queued, a step only launches kernels and can
+ *    be captured in a HIP graph.
  *  - not thread-safe: one thread per pools object (the paper's allocator is
  *    single-process).
  *
