@@ -108,8 +108,8 @@ WORKLOADS = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="uniform_short")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=None)
@@ -201,13 +201,20 @@ def main():
     torch.cuda.synchronize()
     # timed region: exactly `steps` steps, nothing but the path on the stream
     copies[0] = 0
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         one_step()
+        marks[i + 1].record(stream)      # one marker per step: the spread of step times
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     copies_timed = copies[0]
+    per_step_us = np.array([marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps)])
+    step_us = {"median": float(np.median(per_step_us)), "p10": float(np.percentile(per_step_us, 10)),
+               "p90": float(np.percentile(per_step_us, 90)), "min": float(per_step_us.min()),
+               "max": float(per_step_us.max())}
     # the same `steps` steps again with a HIP event pair around every kernel launch (on the
     # launch stream): per-kernel durations for the roofline.  The event pairs cost about 10 us
     # per launch, which is why the headline region above runs without them.
@@ -283,7 +290,7 @@ def main():
     out = {
         "metric": "hybrid_decode_step_achieved_hbm_GBps_batch%d" % sc.batch,
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "us_per_step": ms_per_step * 1e3,
+        "ms_per_step": ms_per_step, "us_per_step": ms_per_step * 1e3, "step_us": step_us,
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
