@@ -105,6 +105,55 @@ WORKLOADS = {
 }
 
 
+def migration_compare(args, spec, sc, chunk):
+    """The same migrations on two fresh copies of the same pools (all units live where the
+    scenario puts them, contents zero): once moving live units with the copy kernel, once by
+    exchanging the physical chunks behind source and destination slot.  Wall time per call,
+    device idle before and after."""
+    import torch
+    from paper_2605_22416_amd import binding as av
+    from paper_2605_22416_amd.session import DeviceSession
+    ratio = spec.ssm_block_bytes // spec.kv_page_bytes
+    plan = [(0, n) for n in (64, 1024, 16384)] + [(1, n) for n in (1, 16, 256)]
+    rows = []
+    setup = {}
+    for mode in ("copy", "remap"):
+        t0 = time.perf_counter()
+        ses = DeviceSession(sc, fill_byte=None, vmm_chunk=chunk, remap=(mode == "remap"))
+        torch.cuda.synchronize()
+        setup[mode] = time.perf_counter() - t0
+        for donor, n in plan:
+            st = av.avmp_stats(ses.p)
+            if n > st["free"][donor]:
+                continue
+            unit = spec.kv_page_bytes if donor == 0 else spec.ssm_block_bytes
+            if mode == "remap" and unit % chunk != 0:
+                continue                     # such a donor copies in either mode
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            rc, res = av.avmp_migrate(ses.p, donor, n)
+            assert rc == av.AVMP_OK, av.avmp_last_error()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t1
+            rows.append({"mode": mode, "donor": "kv" if donor == 0 else "ssm", "units": n,
+                         "live_units_moved": int(res.units_copied), "seconds": dt,
+                         "capacity_units_per_s": n / dt,
+                         "moved_GBps": res.units_copied * unit / dt / 1e9,
+                         "us_per_moved_unit": dt / res.units_copied * 1e6 if res.units_copied
+                         else None})
+            # give the capacity back so that the next entry starts from the same split
+            back = n * spec.kv_page_bytes // spec.ssm_block_bytes if donor == 0 else n * ratio
+            rc, _ = av.avmp_migrate(ses.p, 1 - donor, back)
+            assert rc == av.AVMP_OK, av.avmp_last_error()
+        torch.cuda.synchronize()
+        ses.close()
+    return {"metric": "migration_copy_vs_physical_remap", "unit": "capacity units/s",
+            "config": {"workload": "%s, batch %d, seed %d" % (args.workload, sc.batch, args.seed),
+                       "arena_GB": sc.arena_bytes / 1e9, "vmm_chunk_KiB": chunk // 1024,
+                       "kv_page_bytes": spec.kv_page_bytes, "ssm_block_bytes": spec.ssm_block_bytes},
+            "arena_setup_s": setup, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +168,13 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
     ap.add_argument("--fill-threads", type=int, default=16)
+    ap.add_argument("--backing", choices=("plain", "vmm"), default="plain",
+                    help="vmm: the arena is attached chunk by chunk through the HIP virtual-memory "
+                         "API (the timed step still migrates by copy)")
+    ap.add_argument("--vmm-chunk-kib", type=int, default=2048)
+    ap.add_argument("--migration-compare", action="store_true",
+                    help="instead of the decode benchmark: time migrations of the same pools done "
+                         "by copy and by exchanging physical chunks, on a vmm arena")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (pools, table and kernels are device-local; "
@@ -142,9 +198,19 @@ def main():
     args.batch = wl["batch"] if args.batch is None else args.batch
     args.seed = wl["seed"] if args.seed is None else args.seed
     sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, **wl["scenario"])
+    vmm_chunk = None
+    if args.backing == "vmm" or args.migration_compare:
+        vmm_chunk = args.vmm_chunk_kib * 1024
+        slack = -sc.arena_bytes % vmm_chunk        # the arena must be whole chunks
+        sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, slack_bytes=slack,
+                                  **wl["scenario"])
+        assert sc.arena_bytes % vmm_chunk == 0
+    if args.migration_compare:
+        print(json.dumps(migration_compare(args, spec, sc, vmm_chunk)))
+        return
     inp = inputs.step_inputs(spec, sc.batch, args.seed)
     t0 = time.perf_counter()
-    ses = DeviceSession(sc, fill_byte=None if wl["fill"] else 0)
+    ses = DeviceSession(sc, fill_byte=None if wl["fill"] else 0, vmm_chunk=vmm_chunk, remap=False)
     if wl["fill"]:
         ses.fill(threads=args.fill_threads)
     else:
@@ -300,6 +366,8 @@ def main():
                                % (wl["text"], sc.batch, churn_kv, churn_ssm, mig_pages),
                    "name": args.workload, "batch": sc.batch, "seed": args.seed,
                    "ssm_state_dtype": args.state_dtype,
+                   "arena_backing": args.backing if vmm_chunk is None
+                   else "vmm, %d KiB chunks" % args.vmm_chunk_kib,
                    "arena_GB": sc.arena_bytes / 1e9},
         "ms_per_step_with_kernel_events": (wall_ev / args.steps * 1e3) if wall_ev else None,
         "algorithmic_bytes_per_step": step_bytes,

@@ -280,6 +280,42 @@ typedef struct avmp_profile {
 int avmp_profile_enable(avmp_pools_t* pools, int on);
 int avmp_profile_read(avmp_pools_t* pools, void* stream, avmp_profile_t* out);
 
+/* Migration by physical remap instead of copy: what the paper leaves as the
+ * step after its prototype (Method, "Dynamic Pool Rebalancing": on-demand
+ * physical page remapping; Limitations: mapping virtual addresses to physical
+ * pages dynamically).  An avmp_vmm_arena_t is a device address range reserved
+ * through the HIP virtual-memory API and backed by separate physical chunks of
+ * chunk_bytes each.  Pools created on avmp_vmm_arena_base() and then switched
+ * with avmp_migrate_by_remap() move a live unit out of the vacated range by
+ * exchanging the physical chunks behind its old and its new slot; tables,
+ * capacities, gap and every resolved location come out exactly as with the
+ * copying avmp_migrate (the content of free slots is unspecified in both).
+ *
+ * avmp_vmm_min_chunk: smallest chunk_bytes of the current device (0: no
+ *   virtual-memory support).
+ * avmp_vmm_arena_create: bytes a multiple of chunk_bytes, chunk_bytes a multiple
+ *   of the minimum; AVMP_ERR_INVALID_ARG otherwise, AVMP_ERR_DEVICE when the
+ *   device refuses.  The arena belongs to the current device and to the caller,
+ *   who destroys it after the pools that sit on it.
+ * avmp_migrate_by_remap: arena non-NULL switches remap on, NULL switches back to
+ *   copy.  A pool takes part when each of its slots covers whole chunks: its
+ *   unit size a multiple of chunk_bytes (and, for the SSM pool, whose slots are
+ *   counted down from the top, the usable arena size too); a pool that does not
+ *   keeps copying when it is the donor.  AVMP_ERR_INVALID_ARG (nothing changes)
+ *   if neither pool qualifies or the pools' arena is not the arena's base.
+ * With remap on, avmp_migrate from a qualifying donor first waits for the whole
+ * device (no work that touches the arena may be in flight on any stream) and the
+ * exchanges run on the host, a few driver calls per chunk; units_copied in the
+ * result then counts exchanged units.  A failed exchange leaves part of the
+ * arena unmapped: AVMP_ERR_DEVICE, and pools and arena must be destroyed without
+ * launching anything more on them. */
+typedef struct avmp_vmm_arena avmp_vmm_arena_t;
+uint64_t avmp_vmm_min_chunk(void);
+int avmp_vmm_arena_create(uint64_t bytes, uint64_t chunk_bytes, avmp_vmm_arena_t** out);
+void* avmp_vmm_arena_base(const avmp_vmm_arena_t* arena);
+int avmp_vmm_arena_destroy(avmp_vmm_arena_t* arena);
+int avmp_migrate_by_remap(avmp_pools_t* pools, avmp_vmm_arena_t* arena);
+
 /* Text of the last error raised on the calling thread ("" if none). */
 const char* avmp_last_error(void);
 

@@ -33,8 +33,8 @@ def _load():
     share pointers, so that case is refused."""
     import torch  # noqa: F401
     tlib = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
-    if os.path.exists(tlib):
-        C.CDLL(tlib, mode=C.RTLD_GLOBAL)
+    global hip_runtime
+    hip_runtime = C.CDLL(tlib if os.path.exists(tlib) else "libamdhip64.so", mode=C.RTLD_GLOBAL)
     handle = C.CDLL(LIB_PATH)
     runtimes = set()
     with open("/proc/self/maps") as f:
@@ -49,6 +49,7 @@ def _load():
     return handle
 
 
+hip_runtime = None      # the HIP runtime both torch and the library use (set by _load)
 lib = _load()
 
 AVMP_OK, AVMP_ERR_CAPACITY, AVMP_ERR_INVALID_HANDLE, AVMP_ERR_INVALID_ARG, AVMP_ERR_DEVICE = range(5)
@@ -135,6 +136,15 @@ lib.avmp_policy_state.argtypes = [_P, C.POINTER(avmp_policy_state_t)]
 lib.avmp_alloc_auto.argtypes = [_P, C.c_int, C.c_uint32, _P, _P, C.POINTER(C.c_uint32)]
 lib.avmp_profile_enable.argtypes = [_P, C.c_int]
 lib.avmp_profile_read.argtypes = [_P, _P, C.POINTER(avmp_profile_t)]
+lib.avmp_vmm_min_chunk.argtypes = []
+lib.avmp_vmm_min_chunk.restype = C.c_uint64
+lib.avmp_vmm_arena_create.argtypes = [C.c_uint64, C.c_uint64, C.POINTER(_P)]
+lib.avmp_vmm_arena_base.argtypes = [_P]
+lib.avmp_vmm_arena_base.restype = C.c_void_p
+lib.avmp_vmm_arena_destroy.argtypes = [_P]
+lib.avmp_migrate_by_remap.argtypes = [_P, _P]
+for _f in ("avmp_vmm_arena_create", "avmp_vmm_arena_destroy", "avmp_migrate_by_remap"):
+    getattr(lib, _f).restype = C.c_int
 for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_alloc", "avmp_free",
            "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
            "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read",
@@ -304,3 +314,25 @@ def avmp_alloc_auto(pools, pool: int, n: int, stream=None):
     moved = C.c_uint32()
     rc = lib.avmp_alloc_auto(pools, pool, n, out.ctypes.data, _stream(stream), C.byref(moved))
     return rc, (out[:n] if rc == AVMP_OK else None), moved.value
+
+
+def avmp_vmm_min_chunk() -> int:
+    return int(lib.avmp_vmm_min_chunk())
+
+
+def avmp_vmm_arena_create(nbytes: int, chunk_bytes: int):
+    out = _P()
+    rc = lib.avmp_vmm_arena_create(nbytes, chunk_bytes, C.byref(out))
+    return rc, (out.value if rc == AVMP_OK else None)
+
+
+def avmp_vmm_arena_base(arena) -> int:
+    return int(lib.avmp_vmm_arena_base(arena) or 0)
+
+
+def avmp_vmm_arena_destroy(arena) -> int:
+    return lib.avmp_vmm_arena_destroy(arena)
+
+
+def avmp_migrate_by_remap(pools, arena) -> int:
+    return lib.avmp_migrate_by_remap(pools, arena)

@@ -12,6 +12,7 @@
 #include "../../include/avmp.h"
 #include "kernels.hpp"
 #include "pool_state.hpp"
+#include "vmm_arena.hpp"
 
 namespace {
 
@@ -82,6 +83,10 @@ struct Staging {
 
 }  // namespace
 
+struct avmp_vmm_arena {
+  avmp::VmmArena impl;
+};
+
 struct avmp_pools {
   avmp_config_t cfg{};
   avmp::PoolState st;
@@ -95,6 +100,9 @@ struct avmp_pools {
   std::vector<uint32_t> pending_zero;  // SSM slots to clear
   Staging staging;
   avmp::Rebalancer rebalancer;
+  avmp::VmmArena* remap = nullptr;     // non-null: migrate may exchange backing instead of copying
+  bool remappable[2] = {false, false}; // per pool: every slot covers whole chunks of `remap`
+  bool dead = false;                   // part of the arena lost its mapping: launch nothing
 
   // per-kernel timing: event pairs on the launch stream, summed at read time
   struct ProfRec {
@@ -178,6 +186,7 @@ struct ProfScope {
 // Queue -> device: table entries (coalesced to the last value per index, so the
 // scatter has no ordering hazard) and zero fills of freshly allocated SSM blocks.
 int flush_pending(avmp_pools* p, hipStream_t s) {
+  if (p->dead) return fail(AVMP_ERR_DEVICE, "arena lost its mapping in a failed remap");
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
   if (p->pending.empty() && p->pending_zero.empty()) return AVMP_OK;
   std::vector<avmp::TableUpdate> upd;
@@ -388,7 +397,23 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
   const int rc = p->st.migrate(donor, n, &moves, &remap, &gain, &wasted);
   if (rc != AVMP_OK)
     return fail(rc, rc == AVMP_ERR_CAPACITY ? "donor has too few free units" : "bad donor or n");
-  if (p->has_device && !moves.empty()) {
+  if (p->has_device && p->remap != nullptr && p->remappable[donor]) {
+    if (!moves.empty()) {
+      // nothing may touch a range while its backing changes
+      HIP_TRY(hipDeviceSynchronize());
+      const avmp::Geometry& g = p->st.geometry();
+      const uint64_t unit = g.unit[donor];
+      for (const avmp::Move& m : moves) {
+        const hipError_t e = p->remap->exchange(p->st.byte_offset(donor, m.src_slot),
+                                                p->st.byte_offset(donor, m.dst_slot), unit);
+        if (e != hipSuccess) {
+          p->dead = true;
+          return fail_hip(e, "avmp_migrate: exchanging the backing of two slots");
+        }
+      }
+      p->pending.insert(p->pending.end(), remap.begin(), remap.end());
+    }
+  } else if (p->has_device && !moves.empty()) {
     const size_t bytes = moves.size() * sizeof(avmp::Move);
     Staging::Buf* b = nullptr;
     HIP_TRY(p->staging.acquire(bytes, &b));
@@ -410,9 +435,60 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
   return AVMP_OK;
 }
 
+uint64_t avmp_vmm_min_chunk(void) { return avmp::VmmArena::min_chunk(); }
+
+int avmp_vmm_arena_create(uint64_t bytes, uint64_t chunk_bytes, avmp_vmm_arena_t** out) {
+  if (out == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null out");
+  const uint64_t g = avmp::VmmArena::min_chunk();
+  if (g == 0) return fail(AVMP_ERR_DEVICE, "device has no virtual-memory support");
+  if (bytes == 0 || chunk_bytes == 0 || chunk_bytes % g != 0 || bytes % chunk_bytes != 0)
+    return fail(AVMP_ERR_INVALID_ARG,
+                "bytes must be a multiple of chunk_bytes, chunk_bytes of avmp_vmm_min_chunk()");
+  avmp_vmm_arena* a = new (std::nothrow) avmp_vmm_arena();
+  if (a == nullptr) return fail(AVMP_ERR_INVALID_ARG, "out of host memory");
+  const hipError_t e = a->impl.create(bytes, chunk_bytes);
+  if (e != hipSuccess) {
+    delete a;
+    return fail_hip(e, "avmp_vmm_arena_create");
+  }
+  *out = a;
+  return AVMP_OK;
+}
+
+void* avmp_vmm_arena_base(const avmp_vmm_arena_t* a) { return a ? a->impl.base() : nullptr; }
+
+int avmp_vmm_arena_destroy(avmp_vmm_arena_t* a) {
+  if (a == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null arena");
+  delete a;
+  return AVMP_OK;
+}
+
+int avmp_migrate_by_remap(avmp_pools_t* p, avmp_vmm_arena_t* a) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  if (a == nullptr) {
+    p->remap = nullptr;
+    return AVMP_OK;
+  }
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  const avmp::Geometry& g = p->st.geometry();
+  const uint64_t chunk = a->impl.chunk();
+  if (a->impl.broken() || p->arena != a->impl.base() || g.usable > a->impl.bytes())
+    return fail(AVMP_ERR_INVALID_ARG, "the pools do not sit on this arena");
+  // KV slots start at multiples of their unit, SSM slots at usable minus such multiples
+  const bool kv_ok = g.unit[0] % chunk == 0;
+  const bool ssm_ok = g.unit[1] % chunk == 0 && g.usable % chunk == 0;
+  if (!kv_ok && !ssm_ok)
+    return fail(AVMP_ERR_INVALID_ARG, "no pool's slots cover whole chunks of this arena");
+  p->remap = &a->impl;
+  p->remappable[0] = kv_ok;
+  p->remappable[1] = ssm_ok;
+  return AVMP_OK;
+}
+
 int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
   if (p == nullptr || st == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, "arena lost its mapping in a failed remap");
   if (st->n_layers != 0 && st->layer_kind == nullptr) return fail(AVMP_ERR_INVALID_ARG, "layer_kind");
   uint32_t n_attn = 0, n_ssm = 0;
   for (uint32_t i = 0; i < st->n_layers; ++i) {

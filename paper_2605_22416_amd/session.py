@@ -4,6 +4,7 @@ ABI.  torch supplies device memory and streams only; every step of the path
 runs in the library's kernels."""
 from __future__ import annotations
 
+import ctypes
 from typing import Callable, Dict, Optional
 
 import numpy as np
@@ -54,20 +55,50 @@ def unit_jobs(sc: inputs.Scenario, requests=None):
     return jobs
 
 
+def _hip(name: str, *args):
+    """Call the shared HIP runtime directly (for memory torch cannot wrap)."""
+    fn = getattr(av.hip_runtime, name)
+    fn.restype = ctypes.c_int
+    rc = fn(*args)
+    if rc != 0:
+        raise RuntimeError("%s failed with HIP error %d" % (name, rc))
+
+
 class DeviceSession:
-    def __init__(self, sc: inputs.Scenario, fill_byte: Optional[int] = 0):
+    """vmm_chunk: None puts the arena in a torch tensor; a chunk size in bytes puts it
+    in an arena of the library's own, attached chunk by chunk through the HIP
+    virtual-memory API, and switches migration to exchanging chunks."""
+
+    def __init__(self, sc: inputs.Scenario, fill_byte: Optional[int] = 0,
+                 vmm_chunk: Optional[int] = None, remap: bool = True):
         spec = sc.spec
         self.sc = sc
-        self.arena = torch.empty(sc.arena_bytes, dtype=torch.uint8, device=DEV)
-        if fill_byte is not None:
-            self.arena.fill_(fill_byte)
+        self.vmm = None
+        self.p = None
+        if vmm_chunk is None:
+            self.arena = torch.empty(sc.arena_bytes, dtype=torch.uint8, device=DEV)
+            self.base = self.arena.data_ptr()
+            if fill_byte is not None:
+                self.arena.fill_(fill_byte)
+        else:
+            torch.cuda.init()
+            self.arena = None
+            rc, self.vmm = av.avmp_vmm_arena_create(sc.arena_bytes, vmm_chunk)
+            if rc != av.AVMP_OK:
+                raise RuntimeError("avmp_vmm_arena_create: " + av.avmp_last_error())
+            self.base = av.avmp_vmm_arena_base(self.vmm)
+            if fill_byte is not None:
+                _hip("hipMemset", ctypes.c_void_p(self.base), ctypes.c_int(fill_byte),
+                     ctypes.c_size_t(sc.arena_bytes))
         cfg, self._keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                                          spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate,
                                          sc.kv_capacity, sc.ssm_capacity, slot_rank=sc.slot_rank,
                                          state_dtype=spec.state_dtype)
-        rc, self.p = av.avmp_pools_create(cfg, self.arena, sc.arena_bytes)
+        rc, self.p = av.avmp_pools_create(cfg, self.base, sc.arena_bytes)
         if rc != av.AVMP_OK:
             raise RuntimeError("avmp_pools_create: " + av.avmp_last_error())
+        if self.vmm is not None and remap:
+            self._ok(av.avmp_migrate_by_remap(self.p, self.vmm))
         self.kv = np.full((spec.n_attn, sc.batch, sc.max_pages), 0xFFFFFFFF, dtype=np.uint32)
         self.ssm = np.full((spec.n_ssm, sc.batch), 0xFFFFFFFF, dtype=np.uint32)
         for pool, n, tag in alloc_order(sc):
@@ -97,19 +128,34 @@ class DeviceSession:
             torch.cuda.synchronize()
             av.avmp_pools_destroy(self.p)
             self.p = None
+        if self.vmm is not None:
+            av.avmp_vmm_arena_destroy(self.vmm)
+            self.vmm = None
 
     # ---- unit access by handle (host resolve + a slice of the arena tensor) ----
-    def unit(self, h: int) -> torch.Tensor:
+    def unit_range(self, h: int):
         rc, pool, slot, off = av.avmp_resolve(self.p, int(h))
         self._ok(rc)
-        n = self.sc.spec.kv_page_bytes if pool == 0 else self.sc.spec.ssm_block_bytes
-        return self.arena[off: off + n]
+        return off, self.sc.spec.kv_page_bytes if pool == 0 else self.sc.spec.ssm_block_bytes
 
     def write_unit(self, h: int, data: np.ndarray):
-        self.unit(h).copy_(torch.from_numpy(np.ascontiguousarray(data)))
+        off, n = self.unit_range(h)
+        data = np.ascontiguousarray(data)
+        assert data.nbytes == n
+        if self.arena is not None:
+            self.arena[off: off + n].copy_(torch.from_numpy(data.view(np.uint8).reshape(-1)))
+        else:
+            _hip("hipMemcpy", ctypes.c_void_p(self.base + off), ctypes.c_void_p(data.ctypes.data),
+                 ctypes.c_size_t(n), ctypes.c_int(1))      # host to device
 
     def read_unit(self, h: int) -> np.ndarray:
-        return self.unit(h).cpu().numpy()
+        off, n = self.unit_range(h)
+        if self.arena is not None:
+            return self.arena[off: off + n].cpu().numpy()
+        out = np.empty(n, dtype=np.uint8)
+        _hip("hipMemcpy", ctypes.c_void_p(out.ctypes.data), ctypes.c_void_p(self.base + off),
+             ctypes.c_size_t(n), ctypes.c_int(2))          # device to host
+        return out
 
     def job_handle(self, job) -> int:
         pool, layer, r, i = job

@@ -40,11 +40,29 @@ def _check_states(spec, g, op, ssm_handles_per_layer, what=""):
         assert e.max() <= tol, "%s: state rel err %.3g layer %d" % (what, e.max(), ls)
 
 
-def _both(sc, poison=False, scale_inputs=None):
+BACKINGS = ["copy", "remap"]
+
+
+def _chunk(backing, want=None):
+    """None for an ordinary arena; for "remap" the chunk size of an arena attached
+    through the virtual-memory API (the device's minimum unless `want` is given)."""
+    if backing == "copy":
+        return None
+    from paper_2605_22416_amd import binding as av
+    g = av.avmp_vmm_min_chunk()
+    if g == 0:
+        pytest.skip("device has no virtual-memory support")
+    if want is not None:
+        assert want % g == 0
+        return want
+    return g
+
+
+def _both(sc, poison=False, scale_inputs=None, vmm_chunk=None):
     gh = _harness()
     op, kv, ssm = helpers.build_oracle(sc)
     helpers.fill_oracle(op, sc, kv, ssm, poison=poison, scale_inputs=scale_inputs)
-    g = gh.GpuPools(sc, fill_byte=0xFF if poison else 0)
+    g = gh.GpuPools(sc, fill_byte=0xFF if poison else 0, vmm_chunk=vmm_chunk)
     # allocation parity: the library hands out exactly the oracle's handles
     assert np.array_equal(g.kv, kv) and np.array_equal(g.ssm, ssm)
     if poison:      # fresh blocks must read as zero; everything else unmapped stays NaN bytes
@@ -69,10 +87,12 @@ def _check_translation(g, op, handles):
 
 
 # ---------------------------------------------------------------------------
-def test_tiny_fp32_step_then_migrate_four_pages_and_rerun():
+@pytest.mark.parametrize("backing", BACKINGS)
+def test_tiny_fp32_step_then_migrate_four_pages_and_rerun(backing):
     """Config 1: 1 attention + 1 SSM layer, batch 4, fp32; after the step, 4 KV
     pages of capacity go to the SSM pool and the step is re-run from the same
-    initial state: results must be identical."""
+    initial state: results must be identical.  Once with migration as a copy,
+    once as an exchange of physical chunks."""
     spec = inputs.TINY
     sc = inputs.make_scenario(spec, "tiny", 4, seed=1001)
     sc.kv_capacity, sc.ssm_capacity = 64, 8
@@ -84,7 +104,7 @@ def test_tiny_fp32_step_then_migrate_four_pages_and_rerun():
     from paper_2605_22416_amd import binding as av
     results = []
     for migrate in (False, True):
-        op, g, kv, ssm = _both(sc, poison=True)
+        op, g, kv, ssm = _both(sc, poison=True, vmm_chunk=_chunk(backing))
         if migrate:
             ores = op.migrate(orc.POOL_KV, 4)
             rc, res = av.avmp_migrate(g.p, av.AVMP_POOL_KV, 4)
@@ -200,15 +220,17 @@ def test_untranslatable_handles_are_counted_and_skipped():
     g.close()
 
 
-def test_migration_copies_live_units_bit_exactly_both_directions():
+@pytest.mark.parametrize("backing", BACKINGS)
+def test_migration_moves_live_units_bit_exactly_both_directions(backing):
     """Fill both pools, free a scattering of units, migrate capacity back and
     forth; after each migration every live handle must resolve (host and device)
-    to the oracle's slot and hold byte-identical contents."""
+    to the oracle's slot and hold byte-identical contents, whether the units
+    were copied or their physical chunks exchanged."""
     from paper_2605_22416_amd import binding as av
     spec = inputs.TINY
     rng = np.random.default_rng(31)
     sc = inputs.make_scenario(spec, "tiny", 6, seed=31, ctx=[64, 48, 64, 33, 64, 17], headroom=1.5)
-    op, g, kv, ssm = _both(sc, poison=True)
+    op, g, kv, ssm = _both(sc, poison=True, vmm_chunk=_chunk(backing))
     live_kv = [int(h) for r in range(6) for h in kv[0, r, : sc.n_pages[r]]]
     live_ssm = [int(h) for h in ssm[0]]
     drop = [live_kv[i] for i in rng.choice(len(live_kv), size=7, replace=False)]
@@ -235,13 +257,14 @@ def test_migration_copies_live_units_bit_exactly_both_directions():
     g.close()
 
 
-def test_churn_between_steps_keeps_device_table_in_sync():
+@pytest.mark.parametrize("backing", BACKINGS)
+def test_churn_between_steps_keeps_device_table_in_sync(backing):
     """Alloc / free / migrate between decode steps; the device mirror must follow."""
     from paper_2605_22416_amd import binding as av
     spec = inputs.TINY
     rng = np.random.default_rng(41)
     sc = inputs.make_scenario(spec, "tiny", 4, seed=41, headroom=2.0)
-    op, g, kv, ssm = _both(sc, poison=True)
+    op, g, kv, ssm = _both(sc, poison=True, vmm_chunk=_chunk(backing))
     extra = []
     for it in range(6):
         for _ in range(20):
@@ -322,11 +345,12 @@ def test_decode_step_replayed_from_a_hip_graph_matches_eager_steps():
     graphed.close()
 
 
-def test_alloc_auto_rebalances_on_device_and_keeps_contents():
+@pytest.mark.parametrize("backing", BACKINGS)
+def test_alloc_auto_rebalances_on_device_and_keeps_contents(backing):
     """A capacity error in the KV pool with slack in the SSM pool: the handler
-    migrates SSM capacity on the device (live blocks are copied), the retry
-    succeeds, handles and contents match the oracle's policy run, and the
-    decode step still matches."""
+    migrates SSM capacity on the device (live blocks are copied, or their chunks
+    exchanged), the retry succeeds, handles and contents match the oracle's
+    policy run, and the decode step still matches."""
     from paper_2605_22416_amd import binding as av
     spec = inputs.TINY
     sc = inputs.make_scenario(spec, "tiny", 4, seed=51, ctx=[64, 64, 64, 64])
@@ -335,7 +359,7 @@ def test_alloc_auto_rebalances_on_device_and_keeps_contents():
     prng = np.random.default_rng(3)
     sc.slot_rank = [prng.permutation(sc.arena_bytes // spec.kv_page_bytes).astype(np.uint32),
                     prng.permutation(sc.arena_bytes // spec.ssm_block_bytes).astype(np.uint32)]
-    op, g, kv, ssm = _both(sc, poison=True)
+    op, g, kv, ssm = _both(sc, poison=True, vmm_chunk=_chunk(backing))
     policy = dict(threshold_low=0.1, threshold_high=0.3, migration_batch_size=6,
                   min_rebalance_interval_ops=0)
     rb = orc.Rebalancer(op, orc.Policy(**policy))
@@ -492,4 +516,52 @@ def test_ssm_state_stored_as_bf16(dtype, H, P, N):
     for h, data in before.items():
         assert np.array_equal(g.read_unit(h), data)
         assert av.avmp_resolve(g.p, h)[1:] == op.resolve(h)
+    g.close()
+
+
+def test_remap_migration_at_jamba_unit_sizes_and_argument_checks():
+    """64 KiB pages and 4 MiB blocks on an arena of 64 KiB chunks: a decode step,
+    SSM capacity to the KV pool (live blocks in the vacated range change place by
+    exchanging chunks), a step, KV capacity back, a step; every step against the
+    oracle.  Also what the arena calls refuse."""
+    from paper_2605_22416_amd import binding as av
+    chunk = _chunk("remap", want=65536)
+    assert av.avmp_vmm_arena_create(3 * chunk + 1, chunk)[0] == av.AVMP_ERR_INVALID_ARG
+    assert av.avmp_vmm_arena_create(4 * chunk, chunk + 1)[0] == av.AVMP_ERR_INVALID_ARG
+    assert av.avmp_vmm_arena_create(0, chunk)[0] == av.AVMP_ERR_INVALID_ARG
+    spec = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    sc = inputs.make_scenario(spec, "tiny", 3, seed=77, ctx=[130, 40, 257], headroom=1.5)
+    assert sc.arena_bytes % chunk == 0
+    op, g, kv, ssm = _both(sc, vmm_chunk=chunk)
+    # pools that do not sit on the arena, or whose units are smaller than a chunk, are refused
+    rc, other = av.avmp_vmm_arena_create(32 * chunk, 32 * chunk)
+    assert rc == av.AVMP_OK
+    assert av.avmp_migrate_by_remap(g.p, other) == av.AVMP_ERR_INVALID_ARG
+    assert av.avmp_vmm_arena_destroy(other) == av.AVMP_OK
+    moved = 0
+    for it, (donor, n) in enumerate(((None, 0), (1, 4), (0, 270))):
+        if donor is not None:
+            ores = op.migrate(donor, n)
+            rc, res = av.avmp_migrate(g.p, donor, n)
+            assert rc == ores.code == orc.OK
+            assert (res.units_copied, res.recipient_gain, res.bytes_wasted) == \
+                (ores.units_copied, ores.recipient_gain, ores.bytes_wasted)
+            moved += res.units_copied
+            assert av.avmp_stats(g.p) == op.stats()
+            _check_translation(g, op, list(kv.reshape(-1)) + list(ssm.reshape(-1)))
+        inp = inputs.step_inputs(spec, sc.batch, seed=77, step=it)
+        ref_o, ref_y = _oracle_step(op, sc, kv, ssm, inp)
+        o, y = g.step(inp)
+        _check_outputs(spec, o, y, ref_o, ref_y, "remap it %d" % it)
+    assert moved > 0
+    _check_states(spec, g, op, ssm, "remap")
+    # back to copying on the same arena
+    assert av.avmp_migrate_by_remap(g.p, None) == av.AVMP_OK
+    before = {int(h): g.read_unit(int(h)).copy() for h in ssm.reshape(-1)}
+    ores = op.migrate(1, 9)
+    rc, res = av.avmp_migrate(g.p, 1, 9)
+    assert rc == ores.code == orc.OK and res.units_copied == ores.units_copied > 0
+    for h in before:
+        assert av.avmp_resolve(g.p, h)[1:] == op.resolve(h)
+        assert np.array_equal(g.read_unit(h), before[h])
     g.close()
