@@ -91,6 +91,13 @@ class Shape:
     ssm_headdim: int      # P
     ssm_dstate: int       # N
     state_dtype: str = "f32"   # storage type of the SSM state (bytes_per_element of the block)
+    conv_kernel: int = 0       # K taps of the short causal convolution in front of the
+                               # recurrence; 0 = the block is the recurrent state alone
+
+    @property
+    def conv_dim(self) -> int:
+        """Channels of the convolution: x [H][P], then B [N], then C [N]."""
+        return self.ssm_heads * self.ssm_headdim + 2 * self.ssm_dstate
 
     @property
     def elem_bytes(self) -> int:
@@ -113,6 +120,8 @@ class Shape:
             raw = self.page_tokens * self.per_token_bytes
         else:
             raw = self.state_dim * self.state_bytes    # state_dim x bytes_per_element
+            if self.conv_kernel:                       # + the last K-1 convolution inputs
+                raw += (self.conv_kernel - 1) * self.conv_dim * self.elem_bytes
         return round_up(raw, PAGE_ALIGN)
 
 
@@ -429,17 +438,22 @@ class Pools:
 
     # ---- single-token SSM state update ----------------------------------------
     def ssm_step(self, handles: np.ndarray, x: np.ndarray, dt: np.ndarray, A: np.ndarray,
-                 B: np.ndarray, C: np.ndarray) -> np.ndarray:
+                 B: np.ndarray, C: np.ndarray, exact_inputs: bool = False) -> np.ndarray:
         """For request r, head h, channel p, state index n (state block [H][P][N], fp32):
              a = exp(dt[r,h] * A[h])
              S[h,p,n] <- a * S[h,p,n] + dt[r,h] * x[r,h,p] * B[r,n]
              y[r,h,p] = sum_n S[h,p,n] * C[r,n]          (with the updated S)
         The block is updated in place (stored rounded once to the state dtype);
         y uses the updated value before that rounding.  x: [batch][H][P], B, C: [batch][N]
-        in the element dtype; dt: [batch][H] fp32; A: [H] fp32.  Returns float64."""
+        in the element dtype (float64 as they are if exact_inputs: the outputs of
+        conv_step, which are not rounded on the way); dt: [batch][H] fp32; A: [H] fp32.
+        Returns float64."""
         sh = self.shape
         H, P, N = sh.ssm_heads, sh.ssm_headdim, sh.ssm_dstate
-        xf, Bf, Cf = as_f64(x, sh.dtype), as_f64(B, sh.dtype), as_f64(C, sh.dtype)
+        if exact_inputs:
+            xf, Bf, Cf = (np.asarray(t, dtype=np.float64) for t in (x, B, C))
+        else:
+            xf, Bf, Cf = as_f64(x, sh.dtype), as_f64(B, sh.dtype), as_f64(C, sh.dtype)
         dtf, Af = np.asarray(dt, dtype=np.float64), np.asarray(A, dtype=np.float64)
         batch = len(handles)
         y = np.zeros((batch, H, P), dtype=np.float64)
@@ -462,6 +476,53 @@ class Pools:
                 raw.view(np.uint16)[:] = round_to_bf16_bits(S).reshape(-1)
         return y
 
+    def conv_window(self, h: int) -> np.ndarray:
+        """The last K-1 convolution inputs kept behind the state in block h, as
+        float64 [K-1][conv_dim], oldest token first."""
+        sh = self.shape
+        off = sh.state_dim * sh.state_bytes
+        n = (sh.conv_kernel - 1) * sh.conv_dim * sh.elem_bytes
+        return decode_elements(self.unit_view(h)[off: off + n], sh.dtype).reshape(
+            sh.conv_kernel - 1, sh.conv_dim)
+
+    def conv_step(self, handles: np.ndarray, u: np.ndarray, w: np.ndarray,
+                  b: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        """The short causal depthwise convolution that a Mamba-2 layer (the SSM layer
+        of Background, "Hybrid Mamba-Transformer Architectures") applies to x, B and C
+        before the recurrence, taken one token at a time: with u_t[c] the token's input
+        on channel c and the inputs of the K-1 tokens before it kept in the block,
+             v[c]   = b[c] + sum_{k=0..K-1} w[k][c] * u_{t-(K-1)+k}[c]
+             out[c] = v[c] / (1 + exp(-v[c]))                       (SiLU)
+        after which the kept window moves on by one token (inputs are stored as they
+        came, in the element dtype: no rounding).  A fresh block holds zeros, i.e. the
+        sequence starts after K-1 zero inputs.  u: [batch][conv_dim], w: [K][conv_dim],
+        b: [conv_dim] in the element dtype.  Returns float64 x [batch][H][P],
+        B [batch][N], C [batch][N]."""
+        sh = self.shape
+        K, Cd = sh.conv_kernel, sh.conv_dim
+        H, P, N = sh.ssm_heads, sh.ssm_headdim, sh.ssm_dstate
+        uf, wf, bf = as_f64(u, sh.dtype), as_f64(w, sh.dtype), as_f64(b, sh.dtype)
+        off = sh.state_dim * sh.state_bytes
+        nbytes = (K - 1) * Cd * sh.elem_bytes
+        out = np.zeros((len(handles), Cd), dtype=np.float64)
+        u_raw = np.ascontiguousarray(u)
+        for r in range(len(handles)):
+            res = self.resolve(int(handles[r]))
+            if res is None or res[0] != POOL_SSM:
+                raise KeyError("request %d: not a live SSM handle" % r)
+            raw = self.arena[res[2] + off: res[2] + off + nbytes]
+            past = decode_elements(raw, sh.dtype).reshape(K - 1, Cd)
+            v = bf.copy()
+            for k in range(K - 1):
+                v += wf[k] * past[k]
+            v += wf[K - 1] * uf[r]
+            out[r] = v / (1.0 + np.exp(-v))
+            rows = raw.reshape(K - 1, Cd * sh.elem_bytes)
+            rows[:-1] = rows[1:].copy()
+            rows[-1] = u_raw[r].view(np.uint8)
+        x = out[:, : H * P].reshape(len(handles), H, P)
+        return x, out[:, H * P: H * P + N], out[:, H * P + N:]
+
     # ---- one hybrid decode step ------------------------------------------------
     def append_token(self, handles: np.ndarray, ctx: np.ndarray, k_new: np.ndarray,
                      v_new: np.ndarray) -> None:
@@ -478,7 +539,9 @@ class Pools:
                     q: np.ndarray, ssm_handles: np.ndarray, x: np.ndarray, dt: np.ndarray,
                     A: np.ndarray, B: np.ndarray, C: np.ndarray,
                     k_new: Optional[np.ndarray] = None,
-                    v_new: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+                    v_new: Optional[np.ndarray] = None,
+                    xbc: Optional[np.ndarray] = None, conv_w: Optional[np.ndarray] = None,
+                    conv_b: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
         """Layers in model order (0 = attention, 1 = SSM).  Per-kind arrays are
         indexed by the layer's ordinal among layers of its kind:
         kv_handles [n_attn][batch][max_pages], q [n_attn][batch][Hq][D],
@@ -486,6 +549,10 @@ class Pools:
         A [n_ssm][H], B, C [n_ssm][batch][N].  ctx counts tokens already resident.
         If k_new, v_new ([n_attn][batch][Hkv][D]) are given, each attention layer
         first appends the new token and then attends over ctx + 1 tokens.
+        With a convolution window in the blocks (conv_kernel > 0), x, B and C are
+        ignored: each SSM layer first runs conv_step on xbc [n_ssm][batch][conv_dim]
+        with conv_w [n_ssm][K][conv_dim], conv_b [n_ssm][conv_dim] and feeds its
+        unrounded outputs to the recurrence.
         Returns (o [n_attn]..., y [n_ssm]...)."""
         o, y = [], []
         ia = iss = 0
@@ -498,6 +565,11 @@ class Pools:
                 else:
                     o.append(self.paged_attention(kv_handles[ia], ctx, q[ia]))
                 ia += 1
+            elif self.shape.conv_kernel:
+                xc, Bc, Cc = self.conv_step(ssm_handles[iss], xbc[iss], conv_w[iss], conv_b[iss])
+                y.append(self.ssm_step(ssm_handles[iss], xc, dt[iss], A[iss], Bc, Cc,
+                                       exact_inputs=True))
+                iss += 1
             else:
                 y.append(self.ssm_step(ssm_handles[iss], x[iss], dt[iss], A[iss], B[iss], C[iss]))
                 iss += 1

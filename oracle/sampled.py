@@ -16,7 +16,8 @@ from paper_2605_22416_amd import inputs
 
 def oracle_shape(spec) -> orc.Shape:
     return orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype)
+                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype,
+                     spec.conv_kernel)
 
 
 class RequestReference:
@@ -44,14 +45,18 @@ class RequestReference:
         if not fresh:
             for ls in range(spec.n_ssm):
                 self.pools.unit_view(int(self.ssm[ls, 0]))[:] = inputs.unit_content(
-                    spec, seed, inputs.POOL_SSM, ls, r, 0)
+                    spec, seed, inputs.POOL_SSM, ls, r, 0, scale_inputs=scale_inputs)
 
-    def step(self, inp):
-        """inp: the whole batch's step inputs; returns (o [n_attn][Hq][D], y [n_ssm][H][P]) float64."""
+    def step(self, inp, conv=None):
+        """inp: the whole batch's step inputs; conv: (taps, bias) of the short convolution
+        for models that have one.  Returns (o [n_attn][Hq][D], y [n_ssm][H][P]) float64."""
         r = self.r
         one = {k: (v if k == "A" else v[:, r: r + 1]) for k, v in inp.items()}
+        extra = {}
+        if self.spec.conv_kernel:
+            extra = dict(xbc=one["xbc"], conv_w=conv[0], conv_b=conv[1])
         o, y = self.pools.decode_step(self.spec.layer_kinds, self.kv, self.ctx, one["q"], self.ssm,
-                                      one["x"], one["dt"], one["A"], one["B"], one["C"])
+                                      one["x"], one["dt"], one["A"], one["B"], one["C"], **extra)
         return o[:, 0], y[:, 0]
 
     def state(self, layer: int) -> np.ndarray:

@@ -37,6 +37,8 @@ class ModelSpec:
     layer_kinds: Tuple[int, ...]    # model order; 0 = attention, 1 = SSM
     scale_inputs: bool              # q, K, V, x drawn N(0,1) then scaled by 1/sqrt(head dim)
     state_dtype: str = "f32"        # storage type of the SSM state in its block: "f32" or "bf16"
+    conv_kernel: int = 0            # taps of the short convolution in front of the recurrence;
+                                    # 0 = the block holds the recurrent state alone
 
     @property
     def state_bytes(self) -> int:
@@ -59,8 +61,21 @@ class ModelSpec:
         return self.page_tokens * 2 * self.n_kv_heads * self.head_dim * self.elem_bytes
 
     @property
-    def ssm_block_bytes(self) -> int:
+    def conv_dim(self) -> int:
+        """Channels that pass through the short convolution: x [H][P], then B [N], then C [N]."""
+        return self.ssm_heads * self.ssm_headdim + 2 * self.ssm_dstate
+
+    @property
+    def ssm_state_bytes(self) -> int:
         return self.ssm_heads * self.ssm_headdim * self.ssm_dstate * self.state_bytes
+
+    @property
+    def conv_window_bytes(self) -> int:
+        return (self.conv_kernel - 1) * self.conv_dim * self.elem_bytes if self.conv_kernel else 0
+
+    @property
+    def ssm_block_bytes(self) -> int:
+        return (self.ssm_state_bytes + self.conv_window_bytes + 15) // 16 * 16
 
 
 # one attention + one SSM layer, fp32, 4 query / 2 KV heads x 64, SSM 4 x 32 x 16
@@ -76,6 +91,11 @@ def scaled_down(spec: ModelSpec, n_blocks: int = 1, name: Optional[str] = None) 
     """Same head shapes, fewer layers (n_blocks repeats of 1 attention + 7 SSM)."""
     kinds = tuple(ATTN if i % 8 == 4 else SSM for i in range(8 * n_blocks))
     return replace(spec, name=name or spec.name + "_%dblk" % n_blocks, layer_kinds=kinds)
+
+
+def with_conv(spec: ModelSpec, conv_kernel: int = 4) -> ModelSpec:
+    """Same model whose SSM blocks also hold the last conv_kernel-1 inputs of the short convolution."""
+    return replace(spec, name=spec.name + "_conv%d" % conv_kernel, conv_kernel=conv_kernel)
 
 
 def with_state_dtype(spec: ModelSpec, state_dtype: str) -> ModelSpec:
@@ -202,7 +222,22 @@ def step_inputs(spec: ModelSpec, batch: int, seed: int, step: int = 0,
     A = (-np.exp(rng.uniform(-2.0, 0.0, size=(spec.n_ssm, spec.ssm_heads)))).astype(np.float32)
     B = elements(rng, (spec.n_ssm, batch, spec.ssm_dstate), 0.25, spec.dtype)
     C = elements(rng, (spec.n_ssm, batch, spec.ssm_dstate), 0.25, spec.dtype)
-    return {"q": q, "x": x, "dt": dt, "A": A, "B": B, "C": C}
+    out = {"q": q, "x": x, "dt": dt, "A": A, "B": B, "C": C}
+    if spec.conv_kernel:
+        # what enters the short convolution for this token: x, B and C channels side by side
+        crng = np.random.default_rng([seed, 5, step])
+        out["xbc"] = elements(crng, (spec.n_ssm, batch, spec.conv_dim), xs, spec.dtype)
+    return out
+
+
+def conv_weights(spec: ModelSpec, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Taps [n_ssm][K][conv_dim] ~ N(0, 1/K) (tap K-1 meets the newest token) and
+    bias [n_ssm][conv_dim] ~ N(0, 1/16), both in the element dtype."""
+    rng = np.random.default_rng([seed, 6])
+    K = spec.conv_kernel
+    w = elements(rng, (spec.n_ssm, K, spec.conv_dim), 1.0 / math.sqrt(K), spec.dtype)
+    b = elements(rng, (spec.n_ssm, spec.conv_dim), 0.25, spec.dtype)
+    return w, b
 
 
 def new_token_kv(spec: ModelSpec, batch: int, seed: int, step: int = 0,
@@ -229,8 +264,19 @@ def unit_content(spec: ModelSpec, seed: int, pool: int, layer: int, request: int
         s = 1.0 / math.sqrt(spec.head_dim) if sc else 1.0
         n = spec.kv_page_bytes // spec.elem_bytes
         return elements(rng, n, s, spec.dtype).view(np.uint8)
-    n = spec.ssm_block_bytes // spec.state_bytes
-    return elements(rng, n, 1.0, spec.state_dtype).view(np.uint8)
+    if not spec.conv_kernel:
+        n = spec.ssm_block_bytes // spec.state_bytes
+        return elements(rng, n, 1.0, spec.state_dtype).view(np.uint8)
+    # recurrent state, then the window of the last K-1 convolution inputs [K-1][conv_dim]
+    sc = spec.scale_inputs if scale_inputs is None else scale_inputs
+    s = 1.0 / math.sqrt(spec.ssm_headdim) if sc else 1.0
+    out = np.zeros(spec.ssm_block_bytes, dtype=np.uint8)
+    n = spec.ssm_state_bytes // spec.state_bytes
+    out[: spec.ssm_state_bytes] = elements(rng, n, 1.0, spec.state_dtype).view(np.uint8)
+    m = (spec.conv_kernel - 1) * spec.conv_dim
+    out[spec.ssm_state_bytes: spec.ssm_state_bytes + spec.conv_window_bytes] = \
+        elements(rng, m, s, spec.dtype).view(np.uint8)
+    return out
 
 
 def fill_units(spec: ModelSpec, seed: int, jobs: Sequence[Tuple[int, int, int, int]],

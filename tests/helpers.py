@@ -7,7 +7,8 @@ from paper_2605_22416_amd import inputs
 
 def oracle_shape(spec):
     return orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype)
+                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype,
+                     spec.conv_kernel)
 
 
 def alloc_order(sc):

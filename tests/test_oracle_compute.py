@@ -346,3 +346,147 @@ def test_ssm_step_with_bf16_state_storage():
     xf, Bf = orc.as_f64(x, "bf16"), orc.as_f64(B, "bf16")
     exact = a[:, None, None] * S1 + (dt[0].astype(np.float64)[:, None] * xf[0])[:, :, None] * Bf[0][None, None, :]
     assert (np.abs(p.state_values(h) - exact) <= np.abs(exact) * 2.0 ** -8).all()
+
+
+# ---------------------------------------------------------------------------
+# the short convolution in front of the recurrence (blocks with a window)
+# ---------------------------------------------------------------------------
+def _library_causal_conv_silu(u_seq, w, b):
+    """u_seq [T][C], w [K][C], b [C] float64 -> SiLU(causal depthwise convolution) [T][C],
+    through torch's conv1d over the whole sequence (zeros before the first token)."""
+    K = w.shape[0]
+    x = torch.from_numpy(np.ascontiguousarray(u_seq.T))[None]                  # [1][C][T]
+    wt = torch.from_numpy(np.ascontiguousarray(w.T))[:, None, :]               # [C][1][K]
+    out = torch.nn.functional.conv1d(x, wt, bias=torch.from_numpy(b), padding=K - 1,
+                                     groups=w.shape[1])[0, :, : u_seq.shape[0]]
+    return torch.nn.functional.silu(out).numpy().T
+
+
+@pytest.mark.parametrize("dtype,K", [("f32", 4), ("bf16", 3), ("bf16", 2)])
+def test_conv_step_token_by_token_equals_library_convolution_over_the_sequence(dtype, K):
+    spec = inputs.with_conv(_spec(dtype, 1, 1, 16, H=2, P=4, N=8), K)
+    assert spec.conv_dim == 2 * 4 + 16
+    batch, T = 3, 9
+    sc, p, ssm = _ssm_setup(spec, batch, seed=8)
+    p.arena[:] = 0xFF
+    for r in range(batch):
+        p.unit_view(int(ssm[0, r]))[:] = 0                    # fresh blocks
+    w, b = inputs.conv_weights(spec, seed=8)
+    us, outs = [], []
+    for t in range(T):
+        u = inputs.step_inputs(spec, batch, seed=8, step=t)["xbc"][0]
+        us.append(u)
+        x, B, C = p.conv_step(ssm[0], u, w[0], b[0])
+        assert x.shape == (batch, 2, 4) and B.shape == C.shape == (batch, 8)
+        outs.append(np.concatenate([x.reshape(batch, -1), B, C], axis=1))
+    wf, bf = orc.as_f64(w[0], dtype), orc.as_f64(b[0], dtype)
+    for r in range(batch):
+        seq = np.stack([orc.as_f64(u[r], dtype) for u in us])
+        ref = _library_causal_conv_silu(seq, wf, bf)
+        np.testing.assert_allclose(np.stack([o[r] for o in outs]), ref, rtol=1e-12, atol=1e-14)
+        # the window is the last K-1 inputs, oldest first, stored as they came
+        assert np.array_equal(p.conv_window(int(ssm[0, r])), seq[T - (K - 1):])
+        # the recurrent state in front of the window was not touched
+        assert not p.unit_view(int(ssm[0, r]))[: spec.ssm_state_bytes].any()
+
+
+def test_conv_step_continues_from_a_stored_window():
+    """A block whose window holds inputs a, b, c continues the sequence a, b, c, u0, u1, ..."""
+    spec = inputs.with_conv(_spec("f32", 1, 1, 16, H=1, P=8, N=4), 4)
+    sc, p, ssm = _ssm_setup(spec, 1, seed=9)
+    rng = np.random.default_rng(9)
+    h = int(ssm[0, 0])
+    past = rng.standard_normal((3, spec.conv_dim)).astype(np.float32)
+    blk = p.unit_view(h)
+    blk[spec.ssm_state_bytes: spec.ssm_state_bytes + past.nbytes] = past.view(np.uint8).reshape(-1)
+    assert np.array_equal(p.conv_window(h), past.astype(np.float64))
+    w, b = inputs.conv_weights(spec, seed=9)
+    new = rng.standard_normal((2, 1, spec.conv_dim)).astype(np.float32)
+    got = []
+    for t in range(2):
+        x, B, C = p.conv_step(ssm[0], new[t], w[0], b[0])
+        got.append(np.concatenate([x.reshape(-1), B[0], C[0]]))
+    seq = np.concatenate([past, new[:, 0]]).astype(np.float64)
+    ref = _library_causal_conv_silu(seq, w[0].astype(np.float64), b[0].astype(np.float64))
+    np.testing.assert_allclose(np.stack(got), ref[3:], rtol=1e-12, atol=1e-14)
+
+
+def test_conv_special_cases():
+    spec = inputs.with_conv(_spec("f32", 1, 1, 16, H=1, P=4, N=4), 4)
+    sc, p, ssm = _ssm_setup(spec, 1, seed=10)
+    Cd = spec.conv_dim
+    u = np.linspace(-2.0, 2.0, Cd, dtype=np.float32)[None]
+    zero_w, zero_b = np.zeros((4, Cd), np.float32), np.zeros(Cd, np.float32)
+    # no taps, bias only: SiLU(b), and SiLU(0) = 0
+    bias = np.linspace(-3.0, 3.0, Cd, dtype=np.float32)
+    x, B, C = p.conv_step(ssm[0], u, zero_w, bias)
+    out = np.concatenate([x.reshape(-1), B[0], C[0]])
+    np.testing.assert_allclose(out, bias / (1.0 + np.exp(-bias.astype(np.float64))), rtol=1e-15)
+    # only the newest tap set to one: SiLU of the token itself, whatever the window holds
+    w = zero_w.copy(); w[3] = 1.0
+    x, B, C = p.conv_step(ssm[0], 2 * u, w, zero_b)
+    out = np.concatenate([x.reshape(-1), B[0], C[0]])
+    uf = 2 * u[0].astype(np.float64)
+    np.testing.assert_allclose(out, uf / (1.0 + np.exp(-uf)), rtol=1e-15)
+    # only the oldest tap: the token from three steps ago (u went in first, then 2u, now 3u, 4u)
+    w = zero_w.copy(); w[0] = 1.0
+    p.conv_step(ssm[0], 3 * u, w, zero_b)
+    x, B, C = p.conv_step(ssm[0], 4 * u, w, zero_b)
+    out = np.concatenate([x.reshape(-1), B[0], C[0]])
+    uf = u[0].astype(np.float64)
+    np.testing.assert_allclose(out, uf / (1.0 + np.exp(-uf)), rtol=1e-15)
+    # channel order of the outputs: x [H][P] first, then B, then C
+    assert np.array_equal(x.reshape(-1), out[:4]) and np.array_equal(B[0], out[4:8]) and np.array_equal(C[0], out[8:])
+
+
+def test_decode_step_with_convolution_feeds_unrounded_outputs_to_the_recurrence():
+    """The composed step equals: library convolution of the token, then the (separately
+    pinned) recurrence on those values as they are; inputs x, B, C are ignored."""
+    spec = inputs.with_conv(_spec("bf16", 1, 1, 16, H=2, P=4, N=8), 4)
+    batch = 2
+    sc, pa, ssm = _ssm_setup(spec, batch, seed=11)
+    _, pb, ssm_b = _ssm_setup(spec, batch, seed=11)
+    assert np.array_equal(ssm, ssm_b)
+    for r in range(batch):
+        content = inputs.unit_content(spec, 11, inputs.POOL_SSM, 0, r)
+        pa.unit_view(int(ssm[0, r]))[:] = content
+        pb.unit_view(int(ssm[0, r]))[:] = content
+    w, b = inputs.conv_weights(spec, seed=11)
+    kv = np.full((0, batch, 1), orc.INVALID_HANDLE, dtype=np.uint32)
+    for t in range(3):
+        inp = inputs.step_inputs(spec, batch, seed=11, step=t)
+        windows = [pb.conv_window(int(ssm[0, r])) for r in range(batch)]
+        _, y = pa.decode_step((1,), kv, sc.ctx, inp["q"], ssm, None, inp["dt"], inp["A"], None, None,
+                              xbc=inp["xbc"], conv_w=w, conv_b=b)
+        conv = []
+        for r in range(batch):
+            seq = np.concatenate([windows[r], orc.as_f64(inp["xbc"][0][r], "bf16")[None]])
+            conv.append(_library_causal_conv_silu(seq, orc.as_f64(w[0], "bf16"), orc.as_f64(b[0], "bf16"))[-1])
+        conv = np.stack(conv)
+        yb = pb.ssm_step(ssm[0], conv[:, :8].reshape(batch, 2, 4), inp["dt"][0], inp["A"][0],
+                         conv[:, 8:16], conv[:, 16:], exact_inputs=True)
+        pb.conv_step(ssm[0], inp["xbc"][0], w[0], b[0])          # only to move pb's window on
+        np.testing.assert_allclose(y[0], yb, rtol=1e-11, atol=1e-13)
+        for r in range(batch):
+            assert np.array_equal(pa.unit_view(int(ssm[0, r])), pb.unit_view(int(ssm[0, r])))
+
+
+def test_exact_inputs_equal_encoded_inputs_when_the_values_are_representable():
+    spec = _spec("bf16", 1, 1, 16, H=2, P=3, N=8)
+    sc, pa, ssm = _ssm_setup(spec, 2, seed=12)
+    _, pb, _ = _ssm_setup(spec, 2, seed=12)
+    inp = inputs.step_inputs(spec, 2, seed=12)
+    ya = pa.ssm_step(ssm[0], inp["x"][0], inp["dt"][0], inp["A"][0], inp["B"][0], inp["C"][0])
+    yb = pb.ssm_step(ssm[0], orc.as_f64(inp["x"][0], "bf16"), inp["dt"][0], inp["A"][0],
+                     orc.as_f64(inp["B"][0], "bf16"), orc.as_f64(inp["C"][0], "bf16"), exact_inputs=True)
+    assert np.array_equal(ya, yb) and np.array_equal(pa.arena, pb.arena)
+
+
+def test_block_size_with_a_convolution_window():
+    spec = inputs.with_conv(inputs.JAMBA_MINI, 4)
+    assert spec.conv_dim == 128 * 64 + 2 * 128
+    assert spec.ssm_block_bytes == 4 * 128 * 64 * 128 + 3 * 8448 * 2
+    assert helpers.oracle_shape(spec).unit_bytes(orc.POOL_SSM) == spec.ssm_block_bytes
+    odd = inputs.with_conv(_spec("bf16", 1, 1, 16, H=1, P=3, N=8), 2)      # 19 channels
+    assert odd.ssm_block_bytes == (1 * 3 * 8 * 4 + 19 * 2 + 15) // 16 * 16
+    assert helpers.oracle_shape(odd).unit_bytes(orc.POOL_SSM) == odd.ssm_block_bytes

@@ -58,6 +58,16 @@ MUTATIONS = [
     ("thresholds not validated", "if not (0.0 <= policy.threshold_low < policy.threshold_high <= 1.0):", "if False:"),
     ("migration before any failure", "        if code != ERR_CAPACITY:\n            return code, hs, 0\n        moved = self._capacity_error_handler(pool)",
      "        moved = self._capacity_error_handler(pool) if code != ERR_CAPACITY and self.pools.free_count(pool) == 0 else 0\n        if code != ERR_CAPACITY:\n            return code, hs, moved\n        moved = self._capacity_error_handler(pool)"),
+    ("conv taps reversed", "                v += wf[k] * past[k]", "                v += wf[K - 2 - k] * past[k]"),
+    ("conv newest token meets the oldest tap", "            v += wf[K - 1] * uf[r]", "            v += wf[0] * uf[r]"),
+    ("conv forgets the bias", "            v = bf.copy()", "            v = np.zeros_like(bf)"),
+    ("conv without activation", "            out[r] = v / (1.0 + np.exp(-v))", "            out[r] = v"),
+    ("conv sigmoid of the wrong sign", "            out[r] = v / (1.0 + np.exp(-v))", "            out[r] = v / (1.0 + np.exp(v))"),
+    ("conv window does not advance", "            rows[:-1] = rows[1:].copy()", "            pass"),
+    ("conv window stores the token in the oldest row", "            rows[-1] = u_raw[r].view(np.uint8)", "            rows[0] = u_raw[r].view(np.uint8)"),
+    ("conv hands out C as B", "        return x, out[:, H * P: H * P + N], out[:, H * P + N:]", "        return x, out[:, H * P + N:], out[:, H * P: H * P + N]"),
+    ("block size ignores the conv window", "                raw += (self.conv_kernel - 1) * self.conv_dim * self.elem_bytes", "                raw += 0"),
+    ("decode step skips the convolution", "            elif self.shape.conv_kernel:", "            elif False:"),
 ]
 
 PIN_MODULES = (pins_table, pins_compute, pins_policy)
