@@ -61,10 +61,15 @@ def ssm_bytes(spec):
     x in, y out, B, C, dt and the handle + table entry."""
     e = spec.elem_bytes
     H, P, N = spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate
+    if spec.conv_kernel:
+        # the token's x, B, C channels enter once, before the convolution; its window is read
+        # and written; the fp32 values between convolution and recurrence are not counted
+        return (2 * H * P * N * spec.state_bytes + 2 * spec.conv_window_bytes + spec.conv_dim * e
+                + H * P * 4 + H * 4 + 8)
     return 2 * H * P * N * spec.state_bytes + H * P * e + H * P * 4 + 2 * N * e + H * 4 + 8
 
 
-def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=64):
+def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=64, conv=None):
     """Times the CPU oracle, as it stands, on the first requests of the batch
     (all 32 layers each) until about budget_s seconds of work are done."""
     from oracle.sampled import RequestReference
@@ -73,7 +78,7 @@ def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=64):
     for r in range(min(max_requests, sc.batch)):
         ref = RequestReference(spec, seed, r, int(sc.ctx[r]), bool(sc.fresh[r]))
         t0 = time.perf_counter()
-        ref_o[r], ref_y[r] = ref.step(inp)
+        ref_o[r], ref_y[r] = ref.step(inp, conv)
         elapsed += time.perf_counter() - t0
         nbytes += spec.n_attn * attention_bytes(spec, sc.ctx[r]) + spec.n_ssm * ssm_bytes(spec)
         done.append(r)
@@ -164,6 +169,9 @@ def main():
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--state-dtype", choices=("f32", "bf16"), default="f32",
                     help="storage type of the SSM state blocks (f32 is the headline configuration)")
+    ap.add_argument("--conv-kernel", type=int, default=0, choices=(0, 2, 3, 4),
+                    help="taps of the short convolution in front of the recurrence; the SSM blocks "
+                         "then also hold its window (0, the headline configuration: none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
@@ -194,6 +202,8 @@ def main():
     spec = inputs.JAMBA_MINI
     if args.state_dtype != "f32":
         spec = inputs.with_state_dtype(spec, args.state_dtype)
+    if args.conv_kernel:
+        spec = inputs.with_conv(spec, args.conv_kernel)
     wl = WORKLOADS[args.workload]
     args.batch = wl["batch"] if args.batch is None else args.batch
     args.seed = wl["seed"] if args.seed is None else args.seed
@@ -217,14 +227,15 @@ def main():
         args.no_cpu_baseline = True          # nothing to compare: the arena holds zeros
     setup_s = time.perf_counter() - t0
     stream = torch.cuda.current_stream()
-    st, keep, o, y = ses.prepare_step(inp)
+    conv = inputs.conv_weights(spec, args.seed) if spec.conv_kernel else None
+    st, keep, o, y = ses.prepare_step(inp, conv=conv)
 
     # ---- correctness of the very first step against the oracle sample ----------------
     base, parity = None, None
     ses.launch(st, stream)
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        base, ref_o, ref_y = cpu_baseline(spec, sc, inp, args.seed)
+        base, ref_o, ref_y = cpu_baseline(spec, sc, inp, args.seed, conv=conv)
         o_h, y_h = o.cpu().numpy(), y.cpu().numpy()
         eo = ey = 0.0
         for r in ref_o:
@@ -311,6 +322,12 @@ def main():
 
     kernels = {}
     per_launch = {"attention": attn_layer_bytes, "ssm": ssm_layer_bytes}
+    if spec.conv_kernel:
+        # per kernel, the fp32 x, B, C between the two count: written by one, read by the other
+        H, P, N, e = spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.elem_bytes
+        per_launch["ssm"] = sc.batch * (2 * spec.ssm_state_bytes + 2 * H * P * 4 + 2 * N * 4 + H * 4 + 8)
+        per_launch["conv"] = (sc.batch * (2 * spec.conv_window_bytes + spec.conv_dim * (e + 4) + 8)
+                              + (spec.conv_kernel + 1) * spec.conv_dim * e)
     for name, (ms, n) in prof.items():
         if n:
             k = {"launches": int(n), "avg_us": ms / n * 1e3}
@@ -322,18 +339,17 @@ def main():
         a = kernels["ssm"]["GBps"]
         roofline = {"kernel": "ssm_update_kernel", "bound": "hbm", "achieved": a,
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                    "traffic": ssm_traffic(sc.batch) if args.state_dtype == "f32" else None,
-                    "bytes_per_launch": ssm_layer_bytes,
+                    "traffic": ssm_traffic(sc.batch)
+                    if args.state_dtype == "f32" and not spec.conv_kernel else None,
+                    "bytes_per_launch": per_launch["ssm"],
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
 
     # ---- migration sweep (outside the timed region): pages/s of capacity moved ----------
     sweep = []
-    free_kv = av.avmp_stats(ses.p)["free"][0]
     av.avmp_profile_enable(ses.p, True)
     for n in wl["sweep"]:
-        if n > free_kv:
+        if n > av.avmp_stats(ses.p)["free"][0]:
             continue
-        back = n * spec.kv_page_bytes // spec.ssm_block_bytes
         av.avmp_profile_read(ses.p, stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -343,8 +359,9 @@ def main():
         dt_wall = time.perf_counter() - t1
         rc, pr = av.avmp_profile_read(ses.p, stream)
         kms = pr["migrate_copy"][0]
-        rc2, _ = av.avmp_migrate(ses.p, 1, back, stream)
-        assert rc2 == av.AVMP_OK
+        if res.recipient_gain:       # give it back (what did not make a whole block waits in the gap)
+            rc2, _ = av.avmp_migrate(ses.p, 1, res.recipient_gain, stream)
+            assert rc2 == av.AVMP_OK
         sweep.append({"pages": n, "copied": int(res.units_copied),
                       "pages_per_s_wall": n / dt_wall,
                       "copy_GBps_kernel": (res.units_copied * 2 * spec.kv_page_bytes / (kms * 1e-3) / 1e9)
@@ -365,7 +382,7 @@ def main():
                                "freed and re-allocated) + decode + %d-page migration round trip"
                                % (wl["text"], sc.batch, churn_kv, churn_ssm, mig_pages),
                    "name": args.workload, "batch": sc.batch, "seed": args.seed,
-                   "ssm_state_dtype": args.state_dtype,
+                   "ssm_state_dtype": args.state_dtype, "ssm_conv_kernel": args.conv_kernel,
                    "arena_backing": args.backing if vmm_chunk is None
                    else "vmm, %d KiB chunks" % args.vmm_chunk_kib,
                    "arena_GB": sc.arena_bytes / 1e9},

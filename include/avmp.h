@@ -45,7 +45,7 @@
  *    K element (g, t, d) at element index ((g*(D/x) + d/x)*T + t)*x + d%x
  *    V element (g, t, d) at element index G*T*D + (g*D + d)*T + t
  * An SSM block is [ssm_heads][ssm_headdim][ssm_dstate], row-major, fp32 or bf16
- * (ssm_state_dtype).
+ * (ssm_state_dtype), followed by the convolution window if ssm_conv_kernel is set.
  */
 #ifndef AVMP_H
 #define AVMP_H
@@ -88,6 +88,12 @@ typedef struct avmp_config {
   uint32_t ssm_state_dtype;        /* AVMP_F32 (default, 0) or AVMP_BF16: storage type of the SSM
                                       state in its block (the paper's bytes_per_element).
                                       Arithmetic is fp32 either way; bf16 storage needs N >= 8 */
+  uint32_t ssm_conv_kernel;        /* 0 (default): the block is the recurrent state alone.  2..4: K
+                                      taps of the layer's short causal convolution; the block then
+                                      also keeps, behind the state, the inputs of the last K-1 tokens
+                                      as [K-1][H*P + 2*N] elements (oldest first), and a step takes
+                                      xbc / conv_taps / conv_bias instead of x, B, C.  Needs H*P and
+                                      N to be multiples of 16/element_bytes */
   uint32_t kv_capacity;            /* initial KV pool capacity in pages */
   uint32_t ssm_capacity;           /* initial SSM pool capacity in blocks */
   uint32_t max_vid[2];             /* virtual ids per pool; 0 = as many as slots could ever exist */
@@ -151,11 +157,21 @@ typedef struct avmp_step {
    * ctx itself is not modified. */
   const void* k_new;                 /* device [n_attn][batch][n_kv_heads][head_dim] elements */
   const void* v_new;                 /* device [n_attn][batch][n_kv_heads][head_dim] elements */
+  /* Pools created with ssm_conv_kernel = K take these three instead of x, B and C
+   * (which are then ignored; all three 16-byte aligned).  Each SSM layer first runs
+   * its short convolution for the new token, per channel c of [x (H*P) | B (N) | C (N)]:
+   *   v = conv_bias[c] + sum_k conv_taps[k][c] * input_{t-(K-1)+k}[c],  out = v / (1 + exp(-v)),
+   * tap K-1 meeting xbc and the earlier taps the window kept in the block, which then
+   * moves on by one token; the fp32 outputs feed the recurrence unrounded. */
+  const void* xbc;                   /* device [n_ssm][batch][H*P + 2*N] elements */
+  const void* conv_taps;             /* device [n_ssm][K][H*P + 2*N] elements */
+  const void* conv_bias;             /* device [n_ssm][H*P + 2*N] elements */
 } avmp_step_t;
 
 /* Size arithmetic of Method, "Asymmetric Virtual Page Table": KV page =
  * attention_page_tokens x per_token_bytes (K and V of one attention layer, all
- * KV heads), SSM block = state_dim x bytes_per_element (4 or 2); both rounded up to 16.
+ * KV heads), SSM block = state_dim x bytes_per_element (4 or 2), plus the convolution
+ * window if configured; both rounded up to 16.
  * Host only.  AVMP_ERR_INVALID_ARG on unsupported shapes. */
 int avmp_geometry(const avmp_config_t* cfg, size_t arena_bytes, avmp_geometry_t* out);
 
@@ -271,7 +287,8 @@ enum {
   AVMP_K_SSM = 2,              /* SSM state update (per layer) */
   AVMP_K_MIGRATE_COPY = 3,     /* migration copy + remap */
   AVMP_K_TABLE = 4,            /* table scatter + zero fill of new SSM blocks */
-  AVMP_K_COUNT = 5
+  AVMP_K_CONV = 5,             /* short convolution in front of the recurrence (per layer) */
+  AVMP_K_COUNT = 6
 };
 typedef struct avmp_profile {
   double ms[AVMP_K_COUNT];

@@ -63,7 +63,8 @@ class avmp_config_t(C.Structure):
     _fields_ = [("dtype", C.c_uint32), ("attention_page_tokens", C.c_uint32),
                 ("n_q_heads", C.c_uint32), ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
                 ("ssm_heads", C.c_uint32), ("ssm_headdim", C.c_uint32), ("ssm_dstate", C.c_uint32),
-                ("ssm_state_dtype", C.c_uint32), ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
+                ("ssm_state_dtype", C.c_uint32), ("ssm_conv_kernel", C.c_uint32),
+                ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
                 ("max_vid", C.c_uint32 * 2), ("slot_rank", C.POINTER(C.c_uint32) * 2)]
 
 
@@ -89,12 +90,14 @@ class avmp_step_t(C.Structure):
                 ("max_pages", C.c_uint32), ("kv_handles", C.c_void_p), ("ctx", C.c_void_p),
                 ("q", C.c_void_p), ("o", C.c_void_p), ("ssm_handles", C.c_void_p),
                 ("x", C.c_void_p), ("dt", C.c_void_p), ("A", C.c_void_p), ("B", C.c_void_p),
-                ("C", C.c_void_p), ("y", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p)]
+                ("C", C.c_void_p), ("y", C.c_void_p), ("k_new", C.c_void_p), ("v_new", C.c_void_p),
+                ("xbc", C.c_void_p), ("conv_taps", C.c_void_p), ("conv_bias", C.c_void_p)]
 
 
-AVMP_K_ATTENTION, AVMP_K_ATTENTION_MERGE, AVMP_K_SSM, AVMP_K_MIGRATE_COPY, AVMP_K_TABLE = range(5)
-AVMP_K_COUNT = 5
-KERNEL_NAMES = ("attention", "attention_merge", "ssm", "migrate_copy", "table")
+(AVMP_K_ATTENTION, AVMP_K_ATTENTION_MERGE, AVMP_K_SSM, AVMP_K_MIGRATE_COPY, AVMP_K_TABLE,
+ AVMP_K_CONV) = range(6)
+AVMP_K_COUNT = 6
+KERNEL_NAMES = ("attention", "attention_merge", "ssm", "migrate_copy", "table", "conv")
 
 
 class avmp_profile_t(C.Structure):
@@ -175,7 +178,8 @@ def _stream(s) -> Optional[int]:
 def make_config(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, ssm_heads: int,
                 ssm_headdim: int, ssm_dstate: int, kv_capacity: int, ssm_capacity: int,
                 slot_rank: Optional[Sequence[Optional[np.ndarray]]] = None,
-                max_vid: Sequence[int] = (0, 0), page_tokens: int = 16, state_dtype: str = "f32"):
+                max_vid: Sequence[int] = (0, 0), page_tokens: int = 16, state_dtype: str = "f32",
+                conv_kernel: int = 0):
     """Returns (avmp_config_t, keepalive): keepalive holds the rank arrays the struct points to."""
     cfg = avmp_config_t()
     cfg.dtype = AVMP_F32 if dtype == "f32" else AVMP_BF16
@@ -183,6 +187,7 @@ def make_config(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, ssm_
     cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_q_heads, n_kv_heads, head_dim
     cfg.ssm_heads, cfg.ssm_headdim, cfg.ssm_dstate = ssm_heads, ssm_headdim, ssm_dstate
     cfg.ssm_state_dtype = AVMP_F32 if state_dtype == "f32" else AVMP_BF16
+    cfg.ssm_conv_kernel = conv_kernel
     cfg.kv_capacity, cfg.ssm_capacity = kv_capacity, ssm_capacity
     cfg.max_vid[0], cfg.max_vid[1] = max_vid
     keep = []
@@ -232,7 +237,8 @@ def avmp_migrate(pools, donor_pool: int, n_donor_units: int, stream=None):
 
 
 def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles, ctx, q, o,
-              ssm_handles, x, dt, A, B, Cm, y, k_new=None, v_new=None):
+              ssm_handles, x, dt, A, B, Cm, y, k_new=None, v_new=None, xbc=None, conv_taps=None,
+              conv_bias=None):
     """Returns (avmp_step_t, keepalive).  Tensors must stay alive until the step has run."""
     st = avmp_step_t()
     kinds = np.ascontiguousarray(layer_kinds, dtype=np.uint8)
@@ -242,7 +248,9 @@ def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles
     st.ssm_handles, st.x, st.dt, st.A = _ptr(ssm_handles), _ptr(x), _ptr(dt), _ptr(A)
     st.B, st.C, st.y = _ptr(B), _ptr(Cm), _ptr(y)
     st.k_new, st.v_new = _ptr(k_new), _ptr(v_new)
-    return st, (kinds, kv_handles, ctx, q, o, ssm_handles, x, dt, A, B, Cm, y, k_new, v_new)
+    st.xbc, st.conv_taps, st.conv_bias = _ptr(xbc), _ptr(conv_taps), _ptr(conv_bias)
+    return st, (kinds, kv_handles, ctx, q, o, ssm_handles, x, dt, A, B, Cm, y, k_new, v_new,
+                xbc, conv_taps, conv_bias)
 
 
 def avmp_decode_step(pools, step: avmp_step_t, stream=None) -> int:

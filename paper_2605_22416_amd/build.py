@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libavmp.so")
-SOURCES = ["pool_state.cpp", "kernels.hip", "ssm_update.hip", "attn_mfma.hip", "vmm_arena.hip",
+SOURCES = ["pool_state.cpp", "kernels.hip", "ssm_update.hip", "attn_mfma.hip", "conv_update.hip",
+           "vmm_arena.hip",
            "avmp_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

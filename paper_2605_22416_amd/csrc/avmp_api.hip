@@ -161,6 +161,10 @@ bool shape_from_config(const avmp_config_t* c, avmp::ShapeArgs* s) {
   if (s->state_bytes == 2 && n < 8) return false;      // a lane moves 16 bytes = 8 bf16 of a row
   if (c->ssm_heads == 0 || c->ssm_headdim == 0) return false;
   if (c->ssm_heads > 65535 || c->n_q_heads > 65535) return false;
+  if (c->ssm_conv_kernel != 0 &&
+      !avmp::conv_supported(c->dtype, c->ssm_conv_kernel, c->ssm_heads, c->ssm_headdim, n))
+    return false;
+  s->conv_kernel = c->ssm_conv_kernel;
   s->page_tokens = c->attention_page_tokens;
   s->n_q_heads = c->n_q_heads;
   s->n_kv_heads = c->n_kv_heads;
@@ -503,9 +507,19 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
   if ((st->k_new == nullptr) != (st->v_new == nullptr))
     return fail(AVMP_ERR_INVALID_ARG, "k_new and v_new go together");
   const bool append = st->k_new != nullptr;
-  if (n_ssm && st->batch &&
-      (!st->ssm_handles || !st->x || !st->dt || !st->A || !st->B || !st->C || !st->y))
-    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need ssm_handles, x, dt, A, B, C, y");
+  const bool conv = p->cfg.ssm_conv_kernel != 0;
+  if (n_ssm && st->batch && (!st->ssm_handles || !st->dt || !st->A || !st->y))
+    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need ssm_handles, dt, A, y");
+  if (n_ssm && st->batch && !conv && (!st->x || !st->B || !st->C))
+    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need x, B, C");
+  if (n_ssm && st->batch && conv) {
+    if (!st->xbc || !st->conv_taps || !st->conv_bias)
+      return fail(AVMP_ERR_INVALID_ARG,
+                  "pools with a convolution window need xbc, conv_taps, conv_bias");
+    if ((reinterpret_cast<uintptr_t>(st->xbc) | reinterpret_cast<uintptr_t>(st->conv_taps) |
+         reinterpret_cast<uintptr_t>(st->conv_bias)) & 15u)
+      return fail(AVMP_ERR_INVALID_ARG, "xbc, conv_taps, conv_bias must be 16-byte aligned");
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   int rc = flush_pending(p, s);
   if (rc != AVMP_OK) return rc;
@@ -524,11 +538,17 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
   const size_t plan_words = 4 + (size_t(st->batch) + 2) / 2 * 2 + size_t(runs) * 2;
   const size_t slot_cap = size_t(st->batch) * st->max_pages;           // per attention layer
   const size_t slot_words = mfma ? size_t(n_attn) * slot_cap : 0;
-  if (n_attn) {
-    rc = ensure_workspace(p, (part_floats + plan_words + slot_words) * sizeof(float));
+  // ... and, in front of them, the fp32 outputs of the short convolution of one layer
+  const size_t conv_dim = size_t(c.ssm_heads) * c.ssm_headdim + 2 * size_t(c.ssm_dstate);
+  const size_t conv_floats = (conv && n_ssm) ? (size_t(st->batch) * conv_dim + 3) / 4 * 4 : 0;
+  if (n_attn || conv_floats) {
+    const size_t attn_words = n_attn ? part_floats + plan_words + slot_words : 0;
+    rc = ensure_workspace(p, (conv_floats + attn_words) * sizeof(float));
     if (rc != AVMP_OK) return rc;
   }
-  uint32_t* plan_base = reinterpret_cast<uint32_t*>(p->ws + part_floats);
+  float* const conv_out = p->ws;
+  float* const part_base = p->ws + conv_floats;
+  uint32_t* plan_base = reinterpret_cast<uint32_t*>(part_base + part_floats);
   uint32_t* slots_base = plan_base + plan_words;
   const avmp::DevPools P = p->dev_view();
   uint32_t ia = 0, is = 0;
@@ -549,8 +569,8 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       const size_t row = size_t(st->batch) * c.n_q_heads * c.head_dim;
       a.q = static_cast<const char*>(st->q) + size_t(ia) * row * eb;
       a.o = st->o + size_t(ia) * row;
-      a.part_o = p->ws;
-      a.part_ml = p->ws + part_rows * c.head_dim;
+      a.part_o = part_base;
+      a.part_ml = part_base + part_rows * c.head_dim;
       a.batch = st->batch;
       a.max_pages = st->max_pages;
       a.max_chunks = max_chunks;
@@ -586,11 +606,13 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.P = P;
       a.handles = st->ssm_handles + size_t(is) * st->batch;
       const size_t xrow = size_t(st->batch) * c.ssm_heads * c.ssm_headdim;
-      a.x = static_cast<const char*>(st->x) + size_t(is) * xrow * eb;
+      if (!conv) {
+        a.x = static_cast<const char*>(st->x) + size_t(is) * xrow * eb;
+        a.B = static_cast<const char*>(st->B) + size_t(is) * st->batch * c.ssm_dstate * eb;
+        a.C = static_cast<const char*>(st->C) + size_t(is) * st->batch * c.ssm_dstate * eb;
+      }
       a.dt = st->dt + size_t(is) * st->batch * c.ssm_heads;
       a.A = st->A + size_t(is) * c.ssm_heads;
-      a.B = static_cast<const char*>(st->B) + size_t(is) * st->batch * c.ssm_dstate * eb;
-      a.C = static_cast<const char*>(st->C) + size_t(is) * st->batch * c.ssm_dstate * eb;
       a.y = st->y + size_t(is) * xrow;
       a.batch = st->batch;
       a.heads = c.ssm_heads;
@@ -598,6 +620,35 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       a.dstate = c.ssm_dstate;
       a.dtype = c.dtype;
       a.state_dtype = c.ssm_state_dtype;
+      if (conv) {
+        // x, B and C of this layer come out of the convolution, as fp32
+        avmp::ConvLaunch cv{};
+        cv.P = P;
+        cv.handles = a.handles;
+        cv.u = static_cast<const char*>(st->xbc) + size_t(is) * st->batch * conv_dim * eb;
+        cv.taps = static_cast<const char*>(st->conv_taps) + size_t(is) * c.ssm_conv_kernel * conv_dim * eb;
+        cv.bias = static_cast<const char*>(st->conv_bias) + size_t(is) * conv_dim * eb;
+        cv.x = conv_out;
+        cv.B = conv_out + xrow;
+        cv.C = cv.B + size_t(st->batch) * c.ssm_dstate;
+        cv.state_bytes = uint64_t(c.ssm_heads) * c.ssm_headdim * c.ssm_dstate *
+                         (c.ssm_state_dtype == AVMP_F32 ? 4 : 2);
+        cv.batch = st->batch;
+        cv.heads = c.ssm_heads;
+        cv.headdim = c.ssm_headdim;
+        cv.dstate = c.ssm_dstate;
+        cv.conv_dim = uint32_t(conv_dim);
+        cv.taps_k = c.ssm_conv_kernel;
+        cv.dtype = c.dtype;
+        {
+          ProfScope scope(p, AVMP_K_CONV, s);
+          HIP_TRY(avmp::launch_conv_update(cv, s));
+        }
+        a.x = cv.x;
+        a.B = cv.B;
+        a.C = cv.C;
+        a.dtype = AVMP_F32;
+      }
       {
         ProfScope scope(p, AVMP_K_SSM, s);
         HIP_TRY(avmp::launch_ssm(a, s));

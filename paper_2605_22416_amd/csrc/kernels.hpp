@@ -46,6 +46,23 @@ struct SsmLaunch {
   uint32_t state_dtype;      // storage type of the state block: 0 f32, 1 bf16
 };
 
+struct ConvLaunch {
+  DevPools P;
+  const uint32_t* handles;   // device [batch]: SSM blocks whose window is used and advanced
+  const void* u;             // device [batch][conv_dim] elements: this token's inputs
+  const void* taps;          // device [K][conv_dim] elements, tap K-1 meets the newest token
+  const void* bias;          // device [conv_dim] elements
+  float* x;                  // device [batch][H][P] out
+  float* B;                  // device [batch][N] out
+  float* C;                  // device [batch][N] out
+  uint64_t state_bytes;      // bytes of recurrent state in front of the window
+  uint32_t batch, heads, headdim, dstate, conv_dim, taps_k;
+  uint32_t dtype;            // element type of u, taps, bias and the window: 0 f32, 1 bf16
+};
+
+bool conv_supported(uint32_t dtype, uint32_t taps_k, uint32_t heads, uint32_t headdim,
+                    uint32_t dstate);
+hipError_t launch_conv_update(const ConvLaunch& a, hipStream_t s);
 hipError_t launch_kv_append(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 // matrix-core variant (attn_mfma.hip): bf16, head_dim 64/128/256, query group <= 16

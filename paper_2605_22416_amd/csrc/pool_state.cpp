@@ -65,7 +65,11 @@ bool compute_geometry(const ShapeArgs& s, uint64_t arena_bytes, Geometry* g) {
   // of one layer for all KV heads.  SSM block = state_dim x bytes_per_element.
   uint64_t per_token = 2ull * s.n_kv_heads * s.head_dim * s.elem_bytes;
   g->unit[0] = round_up(uint64_t(s.page_tokens) * per_token, 16);
-  g->unit[1] = round_up(uint64_t(s.ssm_heads) * s.ssm_headdim * s.ssm_dstate * s.state_bytes, 16);
+  uint64_t block = uint64_t(s.ssm_heads) * s.ssm_headdim * s.ssm_dstate * s.state_bytes;
+  if (s.conv_kernel)   // + the inputs of the last K-1 tokens on the x, B and C channels
+    block += uint64_t(s.conv_kernel - 1) *
+             (uint64_t(s.ssm_heads) * s.ssm_headdim + 2ull * s.ssm_dstate) * s.elem_bytes;
+  g->unit[1] = round_up(block, 16);
   g->usable = arena_bytes / 128 * 128;
   for (int p = 0; p < kPools; ++p) {
     uint64_t m = g->usable / g->unit[p];

@@ -55,6 +55,7 @@ struct Counters {
 struct ShapeArgs {
   uint32_t elem_bytes, page_tokens, n_q_heads, n_kv_heads, head_dim, ssm_heads, ssm_headdim,
       ssm_dstate, state_bytes;
+  uint32_t conv_kernel = 0;   // taps of the short convolution; 0 = no window in the SSM block
 };
 
 // Returns false if the shape is unusable (zero sizes, more than 2^30 slots).

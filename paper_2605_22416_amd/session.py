@@ -93,7 +93,7 @@ class DeviceSession:
         cfg, self._keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                                          spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate,
                                          sc.kv_capacity, sc.ssm_capacity, slot_rank=sc.slot_rank,
-                                         state_dtype=spec.state_dtype)
+                                         state_dtype=spec.state_dtype, conv_kernel=spec.conv_kernel)
         rc, self.p = av.avmp_pools_create(cfg, self.base, sc.arena_bytes)
         if rc != av.AVMP_OK:
             raise RuntimeError("avmp_pools_create: " + av.avmp_last_error())
@@ -177,11 +177,15 @@ class DeviceSession:
         torch.cuda.synchronize()
 
     # ---- decode steps ------------------------------------------------------------
-    def prepare_step(self, inp: Dict[str, np.ndarray], k_new=None, v_new=None):
+    def prepare_step(self, inp: Dict[str, np.ndarray], k_new=None, v_new=None, conv=None):
         """Upload one step's activations (and the appended token's K, V rows, if
-        given), allocate outputs, build the descriptor."""
+        given; and the (taps, bias) of the short convolution for models that have
+        one), allocate outputs, build the descriptor."""
         sc, spec = self.sc, self.sc.spec
         d = {k: to_dev(v) for k, v in inp.items()}
+        cw = cb = None
+        if spec.conv_kernel:
+            cw, cb = to_dev(conv[0]), to_dev(conv[1])
         kn = to_dev(k_new) if k_new is not None else None
         vn = to_dev(v_new) if v_new is not None else None
         o = torch.full((spec.n_attn, sc.batch, spec.n_q_heads, spec.head_dim), float("nan"),
@@ -190,15 +194,15 @@ class DeviceSession:
                        dtype=torch.float32, device=DEV)
         st, keep = av.make_step(sc.batch, spec.layer_kinds, self.kv.shape[2], self.kv_dev,
                                 self.ctx_dev, d["q"], o, self.ssm_dev, d["x"], d["dt"], d["A"],
-                                d["B"], d["C"], y, kn, vn)
+                                d["B"], d["C"], y, kn, vn, d.get("xbc"), cw, cb)
         return st, keep, o, y
 
     def launch(self, st, stream=None):
         self._ok(av.avmp_decode_step(self.p, st, stream))
 
-    def step(self, inp: Dict[str, np.ndarray], stream=None, k_new=None, v_new=None):
+    def step(self, inp: Dict[str, np.ndarray], stream=None, k_new=None, v_new=None, conv=None):
         """One decode step; returns (o, y) as numpy float32 and checks the fault counter."""
-        st, keep, o, y = self.prepare_step(inp, k_new, v_new)
+        st, keep, o, y = self.prepare_step(inp, k_new, v_new, conv)
         self.launch(st, stream)
         torch.cuda.synchronize()
         rc, faults = av.avmp_device_faults(self.p)
@@ -214,10 +218,17 @@ class DeviceSession:
         rs = range(self.sc.batch) if requests is None else requests
         out = []
         for r in rs:
-            raw = self.read_unit(int(self.ssm[layer, r]))
+            raw = self.read_unit(int(self.ssm[layer, r]))[: spec.ssm_state_bytes]
             vals = raw.view(np.float32) if spec.state_dtype == "f32" else inputs.bf16_bits_to_f32(raw.view(np.uint16))
             out.append(vals.reshape(spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate))
         return np.stack(out)
+
+    def conv_windows(self, layer: int) -> np.ndarray:
+        """The convolution windows of one SSM layer as raw bytes [batch][window bytes]."""
+        spec = self.sc.spec
+        a, n = spec.ssm_state_bytes, spec.conv_window_bytes
+        return np.stack([self.read_unit(int(self.ssm[layer, r]))[a: a + n]
+                         for r in range(self.sc.batch)])
 
     def translate(self, handles: np.ndarray) -> np.ndarray:
         h = to_dev(np.ascontiguousarray(handles, dtype=np.uint32).reshape(-1))

@@ -565,3 +565,53 @@ def test_remap_migration_at_jamba_unit_sizes_and_argument_checks():
         assert av.avmp_resolve(g.p, h)[1:] == op.resolve(h)
         assert np.array_equal(g.read_unit(h), before[h])
     g.close()
+
+
+@pytest.mark.parametrize("dtype,state_dtype,K,H,P,N", [
+    ("f32", "f32", 4, 4, 32, 16),        # generic fp32 kernels
+    ("bf16", "f32", 4, 8, 64, 128),      # the Mamba-2 head shape (specialised recurrence kernel)
+    ("bf16", "bf16", 3, 8, 64, 128),     # bf16 state blocks, three taps
+    ("bf16", "f32", 2, 3, 8, 8),         # two taps, odd head count
+])
+def test_short_convolution_in_front_of_the_recurrence(dtype, state_dtype, K, H, P, N):
+    """Blocks that also hold the convolution window: six decode steps (the window
+    turns over completely), one request starting from a fresh block.  Windows are
+    compared byte for byte after every step, y and the final state within the
+    tolerance of the dtype."""
+    spec = inputs.ModelSpec("conv", dtype, 16, 8, 2, 64, H, P, N, (1, 0, 1), True,
+                            state_dtype=state_dtype, conv_kernel=K)
+    sc = inputs.make_scenario(spec, "tiny", 5, seed=91, ctx=[40, 16, 70, 1, 33])
+    sc.fresh[3] = True
+    op, g, kv, ssm = _both(sc, poison=True)
+    w, b = inputs.conv_weights(spec, seed=91)
+    a, n = spec.ssm_state_bytes, spec.conv_window_bytes
+    for step in range(6):
+        inp = inputs.step_inputs(spec, sc.batch, seed=91, step=step)
+        ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, None, inp["dt"],
+                                      inp["A"], None, None, xbc=inp["xbc"], conv_w=w, conv_b=b)
+        o, y = g.step(inp, conv=(w, b))
+        _check_outputs(spec, o, y, ref_o, ref_y, "conv step %d" % step)
+        for ls in range(spec.n_ssm):
+            got = g.conv_windows(ls)
+            for r in range(sc.batch):
+                assert np.array_equal(got[r], op.unit_view(int(ssm[ls, r]))[a: a + n]), \
+                    "window of layer %d request %d after step %d" % (ls, r, step)
+    if state_dtype == "f32":
+        _check_states(spec, g, op, ssm, "conv")
+    g.close()
+
+
+def test_convolution_inputs_are_required_and_checked():
+    from paper_2605_22416_amd import binding as av
+    spec = inputs.with_conv(inputs.TINY, 4)
+    sc = inputs.make_scenario(spec, "tiny", 2, seed=92, ctx=[16, 20])
+    op, g, kv, ssm = _both(sc)
+    inp = inputs.step_inputs(spec, sc.batch, seed=92)
+    w, b = inputs.conv_weights(spec, seed=92)
+    st, keep, o, y = g.prepare_step(inp, conv=(w, b))
+    st.conv_bias = None
+    assert av.avmp_decode_step(g.p, st) == av.AVMP_ERR_INVALID_ARG
+    st, keep, o, y = g.prepare_step(inp, conv=(w, b))
+    st.xbc = st.xbc + 4                   # not 16-byte aligned
+    assert av.avmp_decode_step(g.p, st) == av.AVMP_ERR_INVALID_ARG
+    g.close()

@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol():
 def _lib_pools(spec, arena_bytes, kv_cap, ssm_cap, ranks):
     cfg, keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                                spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, kv_cap, ssm_cap,
-                               slot_rank=ranks)
+                               slot_rank=ranks, state_dtype=spec.state_dtype,
+                               conv_kernel=spec.conv_kernel)
     rc, p = av.avmp_pools_create(cfg, None, arena_bytes)
     assert rc == av.AVMP_OK, av.avmp_last_error()
     return p
@@ -43,6 +44,27 @@ def test_geometry_matches_the_size_formulas():
         assert tuple(g.unit_bytes) == (kvb, ssb)
         assert g.usable_bytes == (10 * ssb + 77) // 128 * 128
         assert tuple(g.max_slots) == (g.usable_bytes // kvb, g.usable_bytes // ssb)
+
+
+def test_geometry_with_a_convolution_window():
+    for spec in (inputs.with_conv(inputs.TINY, 3), inputs.with_conv(inputs.JAMBA_MINI, 4),
+                 inputs.with_conv(inputs.with_state_dtype(inputs.JAMBA_MINI, "bf16"), 2)):
+        cfg, _ = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
+                                spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, 1, 1,
+                                state_dtype=spec.state_dtype, conv_kernel=spec.conv_kernel)
+        rc, g = av.avmp_geometry(cfg, 1 << 30)
+        assert rc == av.AVMP_OK
+        assert g.unit_bytes[1] == spec.ssm_block_bytes == \
+            helpers.oracle_shape(spec).unit_bytes(orc.POOL_SSM)
+        assert g.unit_bytes[1] > spec.ssm_state_bytes
+    base = dict(dtype="bf16", n_q_heads=4, n_kv_heads=2, head_dim=64, ssm_heads=4, ssm_headdim=32,
+                ssm_dstate=16, kv_capacity=1, ssm_capacity=1)
+    for bad in (dict(conv_kernel=1), dict(conv_kernel=5), dict(conv_kernel=4, ssm_headdim=3),
+                dict(conv_kernel=4, dtype="f32", ssm_heads=1, ssm_headdim=6)):
+        cfg, _ = av.make_config(**{**base, **bad})
+        assert av.avmp_geometry(cfg, 1 << 30)[0] == av.AVMP_ERR_INVALID_ARG
+    cfg, _ = av.make_config(**{**base, "conv_kernel": 4})
+    assert av.avmp_geometry(cfg, 1 << 30)[0] == av.AVMP_OK
 
 
 def test_create_rejects_bad_configs():
@@ -71,9 +93,10 @@ def _check_same(op, lp):
     assert av.avmp_stats(lp) == op.stats()
 
 
-@pytest.mark.parametrize("seed", [1, 2])
-def test_random_traces_match_the_oracle_bit_for_bit(seed):
-    spec = inputs.TINY
+@pytest.mark.parametrize("seed,conv", [(1, 0), (2, 0), (3, 3)])
+def test_random_traces_match_the_oracle_bit_for_bit(seed, conv):
+    # with a 3-tap convolution window the block is 9472 bytes: units that divide nothing evenly
+    spec = inputs.with_conv(inputs.TINY, conv) if conv else inputs.TINY
     rng = np.random.default_rng(seed)
     kv_cap, ssm_cap = 37, 11
     arena = kv_cap * spec.kv_page_bytes + ssm_cap * spec.ssm_block_bytes + 128 * 5
