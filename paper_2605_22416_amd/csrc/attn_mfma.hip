@@ -70,6 +70,8 @@ __device__ __forceinline__ uint32_t pages_of(uint32_t ctx, uint32_t max_pages) {
   return n > max_pages ? max_pages : n;      // a context beyond the handle row is clamped
 }
 
+constexpr uint32_t kMinRunPages = 4;
+
 // One block: page prefix sums over the batch, run length, and each run's start.
 // plan[0] = total pages, plan[1] = pages per run (ipw).
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restrict__ ctx, uint32_t batch,
@@ -98,7 +100,9 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
     run += pages_of(attended_tokens(ctx, r, append), max_pages);
   }
   const uint32_t total = sums[1023];
-  const uint32_t ipw = total == 0 ? 1 : (total + runs - 1) / runs;
+  // equal shares, but not below kMinRunPages: with few pages in the batch, shorter runs
+  // would only add partial results to merge
+  const uint32_t ipw = max(kMinRunPages, (total + runs - 1) / runs);
   if (tid == 0) {
     prefix[batch] = total;
     plan[0] = total;
@@ -336,71 +340,84 @@ void attn_mfma_kernel(AttnLaunch a) {
 }
 
 // Combines the partial results of one (query head, request) in logical (run) order.
-__global__ __launch_bounds__(64) void attn_merge_runs_kernel(AttnLaunch a) {
-  const uint32_t j = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+// Workgroup of four wavefronts: up to 64 pieces (every request of an ordinary
+// batch) are handled by the first alone; a request spread over more runs (one long
+// request in a small batch) gives every wavefront each fourth group of 64 pieces
+// and the four partial sums are added in wavefront order.
+__global__ __launch_bounds__(256) void attn_merge_runs_kernel(AttnLaunch a) {
+  __shared__ float part_sum[3][256];        // wavefronts 1..3: partial output row (head_dim <= 256)
+  __shared__ float part_l[3];
+  const uint32_t j = blockIdx.x, r = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t D = a.head_dim, Hq = a.n_q_heads, Gq = Hq / a.n_kv_heads;
   const uint32_t g = j / Gq, head = j % Gq;
   float* orow = a.o + (size_t(r) * Hq + j) * D;
-  if (j == 0 && lane == 0 && uint64_t(attended_tokens(a.ctx, r, a.append)) > uint64_t(a.max_pages) * 16u)
+  if (j == 0 && threadIdx.x == 0 &&
+      uint64_t(attended_tokens(a.ctx, r, a.append)) > uint64_t(a.max_pages) * 16u)
     count_fault(a.P);
   const uint32_t start = a.prefix[r], end = a.prefix[r + 1];
   if (start == end) {                       // no resident tokens: zero row
-    for (uint32_t d = lane; d < D; d += 64) orow[d] = 0.f;
+    for (uint32_t d = threadIdx.x; d < D; d += 256) orow[d] = 0.f;
     return;
   }
   const uint32_t ipw = a.plan[1];
   const uint32_t wa = start / ipw, wb = (end - 1) / ipw;
   if (wa == wb) return;                     // one run covered it and wrote the row
   const uint32_t np = wb - wa + 1;
+  const bool wide = np > 64;                // the same for the whole workgroup
+  if (!wide && wave != 0) return;
   auto piece = [&](uint32_t k) -> size_t {  // first piece starts the request (slot 1)
     return ((size_t(g) * a.runs + wa + k) * 2 + (k == 0 ? 1 : 0)) * Gq + head;
   };
-  if (np <= 64) {
-    // lane k holds piece k's statistics; weights are broadcast while the partial
-    // outputs are summed in piece order
-    float mk = -INFINITY, lk = 0.f;
-    if (lane < np) {
-      const size_t idx = piece(lane);
-      mk = a.part_ml[idx * 2];
-      lk = a.part_ml[idx * 2 + 1];
-    }
-    float M = mk;
-    for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-    const float wgt = lane < np ? exp2f(mk - M) : 0.f;
-    float L = lk * wgt;
-    for (int o = 32; o; o >>= 1) L += __shfl_xor(L, o);
-    for (uint32_t d0 = 0; d0 < D; d0 += 64) {
-      const uint32_t d = d0 + lane;
-      float sum = 0.f;
-      uint32_t k = 0;
-      for (; k + 4 <= np; k += 4) {
-        float v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = d < D ? a.part_o[piece(k + u) * D + d] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) sum += v[u] * __shfl(wgt, int(k + u));
-      }
-      for (; k < np; ++k) {
-        const float v = d < D ? a.part_o[piece(k) * D + d] : 0.f;
-        sum += v * __shfl(wgt, int(k));
-      }
-      if (d < D) orow[d] = L > 0.f ? sum / L : 0.f;
-    }
-    return;
-  }
-  // more than 64 pieces (one very long request in a small batch): plain loops
+  // the row maximum over all pieces
   float M = -INFINITY;
   for (uint32_t k = lane; k < np; k += 64) M = fmaxf(M, a.part_ml[piece(k) * 2]);
   for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  // groups of 64 pieces: lane k holds piece k's weight, which is broadcast while the
+  // partial outputs are summed in piece order
   float L = 0.f;
-  for (uint32_t k = 0; k < np; ++k)
-    L += a.part_ml[piece(k) * 2 + 1] * exp2f(a.part_ml[piece(k) * 2] - M);
-  for (uint32_t d = lane; d < D; d += 64) {
-    float sum = 0.f;
-    for (uint32_t k = 0; k < np; ++k)
-      sum += a.part_o[piece(k) * D + d] * exp2f(a.part_ml[piece(k) * 2] - M);
-    orow[d] = L > 0.f ? sum / L : 0.f;
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};      // output dims lane, lane + 64, ...
+  for (uint32_t base = wide ? 64 * wave : 0; base < np; base += wide ? 256 : 64) {
+    const uint32_t cnt = min(64u, np - base);
+    float wgt = 0.f;
+    if (lane < cnt) {
+      const size_t idx = piece(base + lane);
+      wgt = exp2f(a.part_ml[idx * 2] - M);
+      L += a.part_ml[idx * 2 + 1] * wgt;
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint32_t d = 64 * q + lane;
+      if (64 * q >= D) break;
+      uint32_t k = 0;
+      for (; k + 4 <= cnt; k += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = a.part_o[piece(base + k + u) * D + d];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum[q] += v[u] * __shfl(wgt, int(k + u));
+      }
+      for (; k < cnt; ++k) sum[q] += a.part_o[piece(base + k) * D + d] * __shfl(wgt, int(k));
+    }
   }
+  for (int o = 32; o; o >>= 1) L += __shfl_xor(L, o);
+  if (wide) {
+    if (wave != 0) {
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) part_sum[wave - 1][64 * q + lane] = sum[q];
+      if (lane == 0) part_l[wave - 1] = L;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (uint32_t w = 0; w < 3; ++w) {
+      L += part_l[w];
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) sum[q] += part_sum[w][64 * q + lane];
+    }
+  }
+#pragma unroll
+  for (uint32_t q = 0; q < 4; ++q)
+    if (64 * q < D) orow[64 * q + lane] = L > 0.f ? sum[q] / L : 0.f;
 }
 
 }  // namespace
@@ -445,7 +462,7 @@ hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s) {
 }
 
 hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s) {
-  attn_merge_runs_kernel<<<dim3(a.n_q_heads, a.batch), dim3(64), 0, s>>>(a);
+  attn_merge_runs_kernel<<<dim3(a.n_q_heads, a.batch), dim3(256), 0, s>>>(a);
   return hipGetLastError();
 }
 
