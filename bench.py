@@ -349,6 +349,22 @@ def main():
                     "bytes_per_launch": per_launch["ssm"],
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
 
+    # ---- alloc / free churn alone (outside the timed region): host logic + table scatter --
+    n_rounds = 200
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(n_rounds):
+        assert av.avmp_free(ses.p, np.concatenate([ghost_kv, ghost_ssm])) == av.AVMP_OK
+        rc1, ghost_kv = av.avmp_alloc(ses.p, 0, churn_kv)
+        rc2, ghost_ssm = av.avmp_alloc(ses.p, 1, churn_ssm)
+        assert rc1 == av.AVMP_OK and rc2 == av.AVMP_OK
+        assert av.avmp_flush(ses.p, stream) == av.AVMP_OK      # table entries + zero fills of the blocks
+    torch.cuda.synchronize()
+    dt_churn = time.perf_counter() - t1
+    churn = {"handles_per_round": int(churn_kv + churn_ssm), "rounds": n_rounds,
+             "us_per_round": dt_churn / n_rounds * 1e6,
+             "handles_freed_and_allocated_per_s": 2 * (churn_kv + churn_ssm) * n_rounds / dt_churn}
+
     # ---- migration sweep (outside the timed region): pages/s of capacity moved ----------
     sweep = []
     av.avmp_profile_enable(ses.p, True)
@@ -394,7 +410,7 @@ def main():
         "ms_per_step_with_kernel_events": (wall_ev / args.steps * 1e3) if wall_ev else None,
         "algorithmic_bytes_per_step": step_bytes,
         "migrated_pages_per_s": 2 * mig_pages * args.steps / wall,
-        "kernels": kernels, "migration_sweep": sweep, "setup_s": setup_s,
+        "kernels": kernels, "migration_sweep": sweep, "churn": churn, "setup_s": setup_s,
         "roofline": roofline, "cpu_baseline": base, "parity_sample": parity,
     }
     print(json.dumps(out))
