@@ -170,7 +170,7 @@ class Scenario:
 
     @property
     def max_pages(self) -> int:
-        return int(self.n_pages.max()) if len(self.n_pages) else 1
+        return max(1, int(self.n_pages.max())) if len(self.n_pages) else 1
 
 
 def make_scenario(spec: ModelSpec, workload: str, batch: int, seed: int,

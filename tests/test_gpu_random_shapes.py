@@ -1,0 +1,83 @@
+"""GPU parity on seeded random shapes: model shape, layer pattern, batch, contexts
+(zero and ragged included), placement, state storage type and convolution window
+are all drawn per seed; two decode steps each, the second one with a migration in
+between, against the CPU oracle.  Tolerances as in test_gpu_parity.py."""
+import numpy as np
+import pytest
+
+from oracle import avmp_oracle as orc
+from paper_2605_22416_amd import inputs
+from tests import helpers
+from tests.test_gpu_parity import _both, _check_outputs, _check_states, _check_translation
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw(seed):
+    rng = np.random.default_rng([seed, 777])
+    dtype = "bf16" if rng.random() < 0.6 else "f32"
+    vec = 8 if dtype == "bf16" else 4
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    Hq = G * int(rng.choice([1, 2, 3, 4, 8, 16]))
+    D = int(rng.choice([16, 32, 64, 128, 256] if dtype == "bf16" else [4, 12, 32, 64, 100]))
+    state_dtype = "bf16" if rng.random() < 0.35 else "f32"
+    N = int(rng.choice([8, 16, 32, 64, 128, 256] if state_dtype == "bf16" or dtype == "bf16"
+                       else [4, 8, 16, 64, 128]))
+    H = int(rng.integers(1, 7))
+    P = int(rng.choice([1, 3, 8, 24, 32, 64, 128]))
+    K = int(rng.choice([0, 0, 2, 3, 4]))
+    if K and ((H * P) % vec or N % vec):          # the convolution kernel moves 16-byte groups of channels
+        P = int(rng.choice([8, 32, 64]))
+        if N % vec:
+            N = 16
+    kinds = tuple(int(k) for k in rng.integers(0, 2, size=int(rng.integers(2, 5))))
+    if inputs.ATTN not in kinds:
+        kinds = kinds + (inputs.ATTN,)
+    if inputs.SSM not in kinds:
+        kinds = (inputs.SSM,) + kinds
+    spec = inputs.ModelSpec("rand%d" % seed, dtype, 16, Hq, G, D, H, P, N, kinds, bool(rng.random() < 0.7),
+                            state_dtype=state_dtype, conv_kernel=K)
+    batch = int(rng.integers(1, 8))
+    ctx = [int(c) for c in rng.choice([0, 1, 15, 16, 17, 40, 129, 333, 600], size=batch)]
+    return spec, ctx, rng
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shape(seed):
+    from paper_2605_22416_amd import binding as av
+    spec, ctx, rng = _draw(seed)
+    what = "seed %d: %s ctx %s" % (seed, spec, ctx)
+    print(what, flush=True)
+    sc = inputs.make_scenario(spec, "tiny", len(ctx), seed=1000 + seed, ctx=ctx, headroom=1.6)
+    sc.fresh[rng.random(len(ctx)) < 0.3] = True
+    op, g, kv, ssm = _both(sc, poison=True)
+    conv = inputs.conv_weights(spec, seed=seed) if spec.conv_kernel else None
+    extra = dict(xbc=None, conv_w=None, conv_b=None)
+    for step in range(2):
+        if step == 1:                      # capacity moves between the steps, live units with it
+            donor = int(rng.integers(0, 2))
+            n = max(1, int(av.avmp_stats(g.p)["free"][donor]) // 2)
+            ores = op.migrate(donor, n)
+            rc, res = av.avmp_migrate(g.p, donor, n)
+            assert rc == ores.code, what
+            if rc == av.AVMP_OK:
+                assert (res.units_copied, res.recipient_gain, res.bytes_wasted) == \
+                    (ores.units_copied, ores.recipient_gain, ores.bytes_wasted), what
+            assert av.avmp_stats(g.p) == op.stats(), what
+            _check_translation(g, op, list(kv.reshape(-1)) + list(ssm.reshape(-1)))
+        inp = inputs.step_inputs(spec, len(ctx), seed=1000 + seed, step=step)
+        if conv is not None:
+            extra = dict(xbc=inp["xbc"], conv_w=conv[0], conv_b=conv[1])
+        ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, inp["x"], inp["dt"],
+                                      inp["A"], inp["B"], inp["C"], **extra)
+        o, y = g.step(inp, conv=conv)
+        _check_outputs(spec, o, y, ref_o, ref_y, what + " step %d" % step)
+    if spec.state_dtype == "f32":
+        _check_states(spec, g, op, ssm, what)
+    if spec.conv_kernel:
+        a, n = spec.ssm_state_bytes, spec.conv_window_bytes
+        for ls in range(spec.n_ssm):
+            got = g.conv_windows(ls)
+            for r in range(len(ctx)):
+                assert np.array_equal(got[r], op.unit_view(int(ssm[ls, r]))[a: a + n]), what
+    g.close()
