@@ -172,6 +172,9 @@ def main():
     ap.add_argument("--conv-kernel", type=int, default=0, choices=(0, 2, 3, 4),
                     help="taps of the short convolution in front of the recurrence; the SSM blocks "
                          "then also hold its window (0, the headline configuration: none)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the decode part of the step from a HIP graph captured once (churn "
+                         "and migration stay eager; their table updates are flushed before each replay)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
@@ -262,13 +265,32 @@ def main():
     mig_blocks_back = mig_pages * spec.kv_page_bytes // spec.ssm_block_bytes
     copies = [0]
 
+    graph = None
+    if args.graph:
+        # everything from here on runs on one side stream, which is also the capture stream
+        stream = torch.cuda.Stream()
+        torch.cuda.set_stream(stream)
+        assert av.avmp_flush(ses.p, stream) == av.AVMP_OK
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        graph.capture_begin()
+        rc = av.avmp_decode_step(ses.p, st, stream)
+        graph.capture_end()
+        assert rc == av.AVMP_OK, av.avmp_last_error()
+        torch.cuda.synchronize()
+    replay = [graph is not None]
+
     def one_step():
         nonlocal ghost_kv, ghost_ssm
         assert av.avmp_free(ses.p, np.concatenate([ghost_kv, ghost_ssm])) == av.AVMP_OK
         rc1, ghost_kv = av.avmp_alloc(ses.p, 0, churn_kv)
         rc2, ghost_ssm = av.avmp_alloc(ses.p, 1, churn_ssm)
         assert rc1 == av.AVMP_OK and rc2 == av.AVMP_OK
-        ses.launch(st, stream)
+        if replay[0]:
+            assert av.avmp_flush(ses.p, stream) == av.AVMP_OK     # the graph holds no queued updates
+            graph.replay()
+        else:
+            ses.launch(st, stream)
         if mig_pages == 0 or mig_blocks_back == 0:      # no room for a round trip at this size
             return
         rc1, res = av.avmp_migrate(ses.p, 0, mig_pages, stream)
@@ -303,6 +325,7 @@ def main():
     events = not args.no_kernel_events
     wall_ev, prof = None, {}
     if events:
+        replay[0] = False                 # per-kernel events need eager launches
         av.avmp_profile_enable(ses.p, True)
         av.avmp_profile_read(ses.p, stream)
         torch.cuda.synchronize()
@@ -404,6 +427,7 @@ def main():
                                % (wl["text"], sc.batch, churn_kv, churn_ssm, mig_pages),
                    "name": args.workload, "batch": sc.batch, "seed": args.seed,
                    "ssm_state_dtype": args.state_dtype, "ssm_conv_kernel": args.conv_kernel,
+                   "decode_from_hip_graph": bool(args.graph),
                    "arena_backing": args.backing if vmm_chunk is None
                    else "vmm, %d KiB chunks" % args.vmm_chunk_kib,
                    "arena_GB": sc.arena_bytes / 1e9},
