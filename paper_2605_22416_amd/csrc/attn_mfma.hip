@@ -3,15 +3,15 @@
 // and V are read from HBM exactly once.
 //
 // Work split.  For each KV head the (request, page) pairs of the batch, in
-// logical order, form one sequence of `total` pages; it is cut into equal runs
-// of `ipw` pages and wavefront w walks run w, crossing request boundaries as it
-// goes.  A run that covers a whole request writes the output row; otherwise it
-// leaves a partial result (un-normalised sum, running max, running sum) that the
-// merge kernel combines in logical order.  Every wavefront moves the same
-// number of bytes, so the launch has no tail, and the split is a function of
-// the context lengths alone: physical placement and migration cannot change
-// one bit of the result.  A one-block plan kernel computes the page prefix sums
-// and each run's starting (request, page) once per decode step.
+// logical order, form one sequence of pages; it is cut into runs of equal cost
+// (a page costs one, starting a request a few) and wavefront w walks run w,
+// crossing request boundaries as it goes.  A run that covers a whole request
+// writes the output row; otherwise it leaves a partial result (un-normalised
+// sum, running max, running sum) that the merge kernel combines in logical
+// order.  Every wavefront does about the same work, so the launch has no tail,
+// and the split is a function of the context lengths alone: physical placement
+// and migration cannot change one bit of the result.  A one-block plan kernel
+// computes the page prefix sums and each run's stretch once per decode step.
 //
 // The in-page layout is the matrix-core operand order, so operands go from
 // global memory to registers to MFMA with no LDS staging and no conversion:
@@ -71,15 +71,23 @@ __device__ __forceinline__ uint32_t pages_of(uint32_t ctx, uint32_t max_pages) {
 }
 
 constexpr uint32_t kMinRunPages = 4;
+// What starting a request costs a wavefront, in pages' worth of time: the query load
+// that waits on the request index, the refill of the page pipeline, the output row.
+constexpr uint32_t kRequestCost = 5;
 
-// One block: page prefix sums over the batch, run length, and each run's start.
-// plan[0] = total pages, plan[1] = pages per run (ipw).
+// One block: page prefix sums over the batch and the cut of the batch's pages into
+// runs of equal COST.  Request r costs kRequestCost + its pages; on the cost axis it
+// sits at prefix[r] + kRequestCost * r, its page p at that + kRequestCost + p.  Run w
+// takes the pages whose position falls into [w * cpw, (w + 1) * cpw): as pages they
+// are still one contiguous stretch of the batch's page sequence, so desc[w] =
+// (first request, first page in it, first and one-past-last index in that sequence).
+// plan[0] = total pages, plan[1] = cost per run (cpw).
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restrict__ ctx, uint32_t batch,
                                                          uint32_t max_pages, uint32_t runs,
                                                          uint32_t append,
                                                          uint32_t* __restrict__ plan,
                                                          uint32_t* __restrict__ prefix,
-                                                         uint2* __restrict__ desc) {
+                                                         uint4* __restrict__ desc) {
   __shared__ uint32_t sums[1024];
   const uint32_t tid = threadIdx.x;
   const uint32_t seg = (batch + 1023) / 1024;
@@ -100,29 +108,40 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
     run += pages_of(attended_tokens(ctx, r, append), max_pages);
   }
   const uint32_t total = sums[1023];
-  // equal shares, but not below kMinRunPages: with few pages in the batch, shorter runs
-  // would only add partial results to merge
-  const uint32_t ipw = max(kMinRunPages, (total + runs - 1) / runs);
+  const uint64_t total_cost = uint64_t(total) + uint64_t(kRequestCost) * batch;
+  // equal shares, but room for at least kMinRunPages pages: with few pages in the batch,
+  // shorter runs would only add partial results to merge
+  const uint64_t cpw = max(uint64_t(kMinRunPages + kRequestCost), (total_cost + runs - 1) / runs);
   if (tid == 0) {
     prefix[batch] = total;
     plan[0] = total;
-    plan[1] = ipw;
+    plan[1] = uint32_t(cpw);
   }
   __syncthreads();                                          // prefix[] visible to the block
-  for (uint32_t w = tid; w < runs; w += 1024) {
-    const uint64_t item = uint64_t(w) * ipw;
-    if (item >= total) {
-      desc[w] = make_uint2(batch, 0);
-      continue;
+  // first page at or after cost position c: (request, page in it, index in the page sequence)
+  auto first_page_at = [&](uint64_t c, uint32_t* rq, uint32_t* pg) -> uint32_t {
+    if (c >= total_cost) {
+      *rq = batch;
+      *pg = 0;
+      return total;
     }
-    // last r with prefix[r] <= item; requests without pages share their prefix with
-    // the next one, so taking the LAST such r skips them
-    uint32_t a = 0, b = batch;                              // invariant: prefix[a] <= item < prefix[b]
+    // last r whose cost position prefix[r] + kRequestCost * r is <= c
+    uint32_t a = 0, b = batch;
     while (b - a > 1) {
       const uint32_t mid = (a + b) / 2;
-      if (prefix[mid] <= item) a = mid; else b = mid;
+      if (uint64_t(prefix[mid]) + uint64_t(kRequestCost) * mid <= c) a = mid; else b = mid;
     }
-    desc[w] = make_uint2(a, uint32_t(item) - prefix[a]);
+    const uint64_t at = uint64_t(prefix[a]) + uint64_t(kRequestCost) * a + kRequestCost;   // its page 0
+    const uint32_t p = c > at ? uint32_t(c - at) : 0;       // c < position of request a + 1, so p < its pages
+    *rq = a;                                                // (or p = 0 in a request without pages: the
+    *pg = p;                                                //  walk skips it)
+    return prefix[a] + p;
+  };
+  for (uint32_t w = tid; w < runs; w += 1024) {
+    uint32_t r0, p0, r1, p1;
+    const uint32_t first = first_page_at(uint64_t(w) * cpw, &r0, &p0);
+    const uint32_t last = first_page_at(uint64_t(w + 1) * cpw, &r1, &p1);
+    desc[w] = make_uint4(r0, p0, first, last);
   }
 }
 
@@ -155,11 +174,10 @@ void attn_mfma_kernel(AttnLaunch a) {
   constexpr int NT = D / 16;
   const uint32_t g = blockIdx.x, w = blockIdx.y;
   const uint32_t lane = threadIdx.x, n = lane & 15, jg = lane >> 4;
-  const uint32_t total = a.plan[0], ipw = a.plan[1];
-  uint64_t item = uint64_t(w) * ipw;
-  if (item >= total) return;
-  const uint64_t item_end = min(uint64_t(total), item + ipw);
-  const uint2 start = a.desc[w];
+  const uint4 start = a.desc[w];
+  uint64_t item = start.z;                     // position in the batch's page sequence
+  const uint64_t item_end = start.w;
+  if (item >= item_end) return;
   uint32_t r = start.x, page = start.y;
   // the run's first 64 slots (for the usual run lengths: all of them), requested before
   // anything that depends on the context lengths
@@ -359,8 +377,10 @@ __global__ __launch_bounds__(256) void attn_merge_runs_kernel(AttnLaunch a) {
     for (uint32_t d = threadIdx.x; d < D; d += 256) orow[d] = 0.f;
     return;
   }
-  const uint32_t ipw = a.plan[1];
-  const uint32_t wa = start / ipw, wb = (end - 1) / ipw;
+  // the runs that hold the request's first and last page (positions on the plan's cost axis)
+  const uint64_t cpw = a.plan[1];
+  const uint64_t at = uint64_t(start) + uint64_t(kRequestCost) * r + kRequestCost;
+  const uint32_t wa = uint32_t(at / cpw), wb = uint32_t((at + (end - start) - 1) / cpw);
   if (wa == wb) return;                     // one run covered it and wrote the row
   const uint32_t np = wb - wa + 1;
   const bool wide = np > 64;                // the same for the whole workgroup
@@ -439,7 +459,7 @@ hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s) {
   attn_plan_kernel<<<dim3(1), dim3(1024), 0, s>>>(a.ctx, a.batch, a.max_pages, a.runs, a.append,
                                                   const_cast<uint32_t*>(a.plan),
                                                   const_cast<uint32_t*>(a.prefix),
-                                                  const_cast<uint2*>(a.desc));
+                                                  const_cast<uint4*>(a.desc));
   return hipGetLastError();
 }
 

@@ -534,8 +534,9 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
   const uint32_t max_chunks = worst < avmp::kMaxChunks ? worst : avmp::kMaxChunks;
   const size_t part_rows = mfma ? size_t(runs) * 2 * c.n_q_heads
                                 : size_t(st->batch) * max_chunks * c.n_q_heads;
-  const size_t part_floats = part_rows * (size_t(c.head_dim) + 2);
-  const size_t plan_words = 4 + (size_t(st->batch) + 2) / 2 * 2 + size_t(runs) * 2;
+  const size_t part_floats = (part_rows * (size_t(c.head_dim) + 2) + 3) / 4 * 4;   // keeps the plan 16-byte aligned
+  const size_t prefix_words = (size_t(st->batch) + 4) / 4 * 4;             // batch + 1 entries
+  const size_t plan_words = 4 + prefix_words + size_t(runs) * 4;
   const size_t slot_cap = size_t(st->batch) * st->max_pages;           // per attention layer
   const size_t slot_words = mfma ? size_t(n_attn) * slot_cap : 0;
   // ... and, in front of them, the fp32 outputs of the short convolution of one layer
@@ -560,7 +561,7 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
       if (mfma) {
         a.plan = plan_base;
         a.prefix = plan_base + 4;
-        a.desc = reinterpret_cast<const uint2*>(plan_base + 4 + (size_t(st->batch) + 2) / 2 * 2);
+        a.desc = reinterpret_cast<const uint4*>(plan_base + 4 + prefix_words);
         a.runs = runs;
         a.slots = slots_base + size_t(ia) * slot_cap;
       }

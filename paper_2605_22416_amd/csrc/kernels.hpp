@@ -25,9 +25,10 @@ struct AttnLaunch {
   const void* k_new;         // device [batch][Hkv][D] (append only)
   const void* v_new;         // device [batch][Hkv][D] (append only)
   // matrix-core path only: balanced runs (see attn_mfma.hip)
-  const uint32_t* plan;      // device [2]: total pages, pages per run
+  const uint32_t* plan;      // device [2]: total pages, cost per run
   const uint32_t* prefix;    // device [batch + 1]: page prefix sums
-  const uint2* desc;         // device [runs]: each run's starting (request, page)
+  const uint4* desc;         // device [runs]: each run's first (request, page) and its stretch
+                             // [first, last) of the batch's page sequence
   const uint32_t* slots;     // device [total pages]: this layer's pre-translated slots, run order
   uint32_t runs;             // runs (wavefronts) per KV head
 };
