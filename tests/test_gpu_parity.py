@@ -615,3 +615,9 @@ def test_convolution_inputs_are_required_and_checked():
     st.xbc = st.xbc + 4                   # not 16-byte aligned
     assert av.avmp_decode_step(g.p, st) == av.AVMP_ERR_INVALID_ARG
     g.close()
+
+
+def test_smoke_entry_point_runs():
+    """The repository's one-call check (a tiny step and a migration against the oracle)."""
+    import __graft_entry__
+    __graft_entry__.smoke()
