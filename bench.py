@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the SSM kernel at this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs scaled by the same counters' readings for the plain migration copy (summary under
 # profiles/).  Valid only for the kernel source it was measured on: reported as null otherwise.
-SSM_TRAFFIC = {"source_sha256_16": "4bf331be2c9d3a94", "batch": 64, "bytes_per_launch": 527271 * 1024}
+SSM_TRAFFIC = {"source_sha256_16": "8e85746839f00ea0", "batch": 64, "bytes_per_launch": 527271 * 1024}
 
 
 def ssm_traffic(batch):
@@ -36,8 +36,9 @@ def ssm_traffic(batch):
     src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "ssm_update.hip")
     try:
         text = open(src).read()
-        # the fp32-state kernel only: from its signature to the start of the bf16-state section
-        i = text.index("void ssm_update_kernel(SsmLaunch a) {")
+        # the fp32-state kernel and the access helpers it streams its tile with: from the
+        # helpers' comment to the start of the bf16-state section
+        i = text.index("// The state tile goes through buffer accesses")
         j = text.index("// Same update with the state stored as bf16")
         digest = hashlib.sha256(text[i:j].encode()).hexdigest()[:16]
     except (OSError, ValueError):

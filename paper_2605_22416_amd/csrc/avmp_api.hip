@@ -161,6 +161,8 @@ bool shape_from_config(const avmp_config_t* c, avmp::ShapeArgs* s) {
   if (s->state_bytes == 2 && n < 8) return false;      // a lane moves 16 bytes = 8 bf16 of a row
   if (c->ssm_heads == 0 || c->ssm_headdim == 0) return false;
   if (c->ssm_heads > 65535 || c->n_q_heads > 65535) return false;
+  // one head's state tile is addressed with 32-bit byte offsets
+  if (uint64_t(c->ssm_headdim) * n * 4 >= (1ull << 31)) return false;
   if (c->ssm_conv_kernel != 0 &&
       !avmp::conv_supported(c->dtype, c->ssm_conv_kernel, c->ssm_heads, c->ssm_headdim, n))
     return false;
