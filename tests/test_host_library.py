@@ -172,3 +172,13 @@ def test_jamba_shaped_allocation_order_matches_the_oracle():
         assert av.avmp_resolve(lp, int(h))[1:] == op.resolve(int(h))
     _check_same(op, lp)
     av.avmp_pools_destroy(lp)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path is a one-GPU path: the benchmark says so instead of running."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
