@@ -29,18 +29,19 @@ def _first_layers(inp, n_attn, n_ssm):
     return {k: (v[:n_attn] if k == "q" else v[:n_ssm]) for k, v in inp.items()}
 
 
-def _check_sample(ses, refs, inp, o, y, what):
+def _check_sample(ses, refs, inp, o, y, what, conv=None, tol_state=TOL, tol_y=TOL):
     """refs: request -> RequestReference, built on the full model or on its first layers."""
     for r, ref in refs.items():
         na, ns = ref.spec.n_attn, ref.spec.n_ssm
-        ro, ry = ref.step(_first_layers(inp, na, ns))
+        ro, ry = ref.step(_first_layers(inp, na, ns),
+                          None if conv is None else (conv[0][:ns], conv[1][:ns]))
         eo = helpers.rel_err_rows(o[:na, r], ro).max() if ro.size else 0.0
         ey = helpers.rel_err_rows(y[:ns, r], ry).max()
         assert np.isfinite(o[:, r]).all() and np.isfinite(y[:, r]).all()
-        assert eo <= TOL and ey <= TOL, "%s request %d: attention %.3g ssm %.3g" % (what, r, eo, ey)
+        assert eo <= TOL and ey <= tol_y, "%s request %d: attention %.3g ssm %.3g" % (what, r, eo, ey)
         for ls in sorted({0, ns - 1}):
             got = ses.states(ls, [r])[0]
-            assert helpers.rel_err_rows(got, ref.state(ls)).max() <= TOL, "%s state r=%d" % (what, r)
+            assert helpers.rel_err_rows(got, ref.state(ls)).max() <= tol_state, "%s state r=%d" % (what, r)
 
 
 def _sample(sc, k, rng, always=()):
@@ -83,6 +84,35 @@ def test_jamba_batch64_uniform_short_full_size():
         inp = inputs.step_inputs(spec, sc.batch, sc.seed, step=step)
         o, y = ses.step(inp)
         _check_sample(ses, refs, inp, o, y, "cfg2 step %d" % step)
+    ses.close()
+
+
+@pytest.mark.parametrize("state_dtype,conv_kernel", [("f32", 4), ("bf16", 0), ("bf16", 4)])
+def test_jamba_batch64_variants_of_the_ssm_block(state_dtype, conv_kernel):
+    """Config 2's batch, contexts and head shapes (one block of 1 attention + 7 SSM
+    layers) with the block variants: state stored as bf16, a 4-tap convolution
+    window, both.  Three steps, sampled requests.  With a bf16 state the stored
+    codes of the two sides part by one ulp where the exact value sits on a rounding
+    tie (fp32 against float64 arithmetic), so from the second step on both start
+    from slightly different states: the state is then compared to one bf16 ulp
+    (2^-7) of its row maximum per step taken, and y to one ulp."""
+    base = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    spec = inputs.with_state_dtype(base, state_dtype) if state_dtype != "f32" else base
+    if conv_kernel:
+        spec = inputs.with_conv(spec, conv_kernel)
+    sc = inputs.make_scenario(spec, "uniform_short", 64, seed=1002)
+    ses = _session(sc, fill_byte=None)
+    ses.fill(threads=16)
+    conv = inputs.conv_weights(spec, sc.seed) if conv_kernel else None
+    rng = np.random.default_rng(5)
+    sample = _sample(sc, 5, rng)
+    refs = {r: RequestReference(spec, sc.seed, r, int(sc.ctx[r])) for r in sample}
+    for step in range(3):
+        inp = inputs.step_inputs(spec, sc.batch, sc.seed, step=step)
+        o, y = ses.step(inp, conv=conv)
+        _check_sample(ses, refs, inp, o, y, "%s conv %d step %d" % (state_dtype, conv_kernel, step),
+                      conv=conv, tol_state=TOL if state_dtype == "f32" else 2.0 ** -7 * (step + 1),
+                      tol_y=TOL if state_dtype == "f32" or step == 0 else 2.0 ** -7)
     ses.close()
 
 
