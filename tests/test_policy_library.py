@@ -117,3 +117,23 @@ def test_dynamic_rebalancing_lowers_capacity_errors_on_a_shifting_mix():
             assert av.avmp_stats(lp)["migrations"] == 0
         av.avmp_pools_destroy(lp)
     assert fails[True] < fails[False], fails
+
+
+def test_trace_driver_dynamic_split_has_fewest_capacity_errors_across_workloads():
+    """The serving-trace driver on the three workload shapes: each static split is
+    right for some shapes and wrong for others, the dynamic one follows the load.
+    Direction only, on synthetic arrivals (the paper's counts are not reproduced)."""
+    from paper_2605_22416_amd import trace_driver
+    totals = {"static 0.5": 0, "static 0.9": 0, "dynamic": 0}
+    per = {}
+    for workload in ("uniform_short", "mixed_long", "agentic_burst"):
+        for name, dynamic, share in (("static 0.5", False, 0.5), ("static 0.9", False, 0.9),
+                                     ("dynamic", True, 0.5)):
+            errs = sum(trace_driver.run_trace(workload, s, dynamic, share, ticks=1500)["capacity_errors"]
+                       for s in range(2))
+            totals[name] += errs
+            per[(workload, name)] = errs
+    assert totals["dynamic"] < totals["static 0.5"] and totals["dynamic"] < totals["static 0.9"], totals
+    # and it never does worse than the split it started from
+    for workload in ("uniform_short", "mixed_long", "agentic_burst"):
+        assert per[(workload, "dynamic")] <= 1.1 * per[(workload, "static 0.5")], per
