@@ -181,10 +181,14 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
     ap.add_argument("--fill-threads", type=int, default=16)
-    ap.add_argument("--backing", choices=("plain", "vmm"), default="plain",
-                    help="vmm: the arena is attached chunk by chunk through the HIP virtual-memory "
-                         "API (the timed step still migrates by copy)")
-    ap.add_argument("--vmm-chunk-kib", type=int, default=2048)
+    ap.add_argument("--backing", choices=("plain", "vmm"), default="vmm",
+                    help="vmm (default): the arena comes from the library's own allocator, attached "
+                         "through the HIP virtual-memory API in large physically contiguous chunks "
+                         "(measured 1.4 %% faster than one ordinary allocation); plain: a torch tensor. "
+                         "The timed step migrates by copy either way")
+    ap.add_argument("--vmm-chunk-kib", type=int, default=None,
+                    help="chunk size of the vmm arena (default 1 GiB; 2 MiB for --migration-compare, "
+                         "where units must be whole chunks)")
     ap.add_argument("--migration-compare", action="store_true",
                     help="instead of the decode benchmark: time migrations of the same pools done "
                          "by copy and by exchanging physical chunks, on a vmm arena")
@@ -214,7 +218,12 @@ def main():
     args.seed = wl["seed"] if args.seed is None else args.seed
     sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, **wl["scenario"])
     vmm_chunk = None
+    if args.backing == "vmm" and not args.migration_compare and av.avmp_vmm_min_chunk() == 0:
+        print("bench.py: this device has no virtual-memory support; using --backing plain", file=sys.stderr)
+        args.backing = "plain"
     if args.backing == "vmm" or args.migration_compare:
+        if args.vmm_chunk_kib is None:
+            args.vmm_chunk_kib = 2048 if args.migration_compare else 1 << 20
         vmm_chunk = args.vmm_chunk_kib * 1024
         slack = -sc.arena_bytes % vmm_chunk        # the arena must be whole chunks
         sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, slack_bytes=slack,
