@@ -181,11 +181,10 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
     ap.add_argument("--fill-threads", type=int, default=16)
-    ap.add_argument("--backing", choices=("plain", "vmm"), default="vmm",
-                    help="vmm (default): the arena comes from the library's own allocator, attached "
-                         "through the HIP virtual-memory API in large physically contiguous chunks "
-                         "(measured 1.4 %% faster than one ordinary allocation); plain: a torch tensor. "
-                         "The timed step migrates by copy either way")
+    ap.add_argument("--backing", choices=("plain", "vmm"), default="plain",
+                    help="plain (default): the arena is a torch tensor; vmm: it comes from the library's "
+                         "own allocator, attached through the HIP virtual-memory API in chunks (same "
+                         "speed with large chunks).  The timed step migrates by copy either way")
     ap.add_argument("--vmm-chunk-kib", type=int, default=None,
                     help="chunk size of the vmm arena (default 1 GiB; 2 MiB for --migration-compare, "
                          "where units must be whole chunks)")
@@ -217,6 +216,15 @@ def main():
     args.batch = wl["batch"] if args.batch is None else args.batch
     args.seed = wl["seed"] if args.seed is None else args.seed
     sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, **wl["scenario"])
+    # SSM blocks count down from the top of the arena.  4 MiB blocks on 4 MiB boundaries measured
+    # 87.1 us per SSM layer against 88.5 us at a 64 KiB-granular offset and 91.5 us at an odd
+    # multiple of 2 MiB, so the arena's size is made a multiple of 4 MiB for them; 2 MiB blocks
+    # (bf16 state) measured 1 % better where the pool sizes happen to put them, and stay there
+    block_pow2 = spec.ssm_block_bytes & -spec.ssm_block_bytes
+    slack = -sc.arena_bytes % block_pow2 if block_pow2 >= (4 << 20) else 0
+    if slack:
+        sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, slack_bytes=slack,
+                                  **wl["scenario"])
     vmm_chunk = None
     if args.backing == "vmm" and not args.migration_compare and av.avmp_vmm_min_chunk() == 0:
         print("bench.py: this device has no virtual-memory support; using --backing plain", file=sys.stderr)
@@ -225,7 +233,7 @@ def main():
         if args.vmm_chunk_kib is None:
             args.vmm_chunk_kib = 2048 if args.migration_compare else 1 << 20
         vmm_chunk = args.vmm_chunk_kib * 1024
-        slack = -sc.arena_bytes % vmm_chunk        # the arena must be whole chunks
+        slack += -sc.arena_bytes % vmm_chunk       # the arena must be whole chunks
         sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, slack_bytes=slack,
                                   **wl["scenario"])
         assert sc.arena_bytes % vmm_chunk == 0
