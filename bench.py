@@ -32,6 +32,23 @@ PREWARM_STEPS = 10
 SSM_TRAFFIC = {"source_sha256_16": "8e85746839f00ea0", "batch": 64, "bytes_per_launch": 527271 * 1024}
 
 
+# The same for the attention kernel (whole source file hashed).
+ATTN_TRAFFIC = {"source_sha256_16": "408a3bb3b3798060", "batch": 64, "bytes_per_launch": 272775 * 1024}
+
+
+def attn_traffic(batch, workload, seed):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "attn_mfma.hip")
+    try:
+        digest = hashlib.sha256(open(src).read().encode()).hexdigest()[:16]
+    except OSError:
+        return None
+    if (digest != ATTN_TRAFFIC["source_sha256_16"] or batch != ATTN_TRAFFIC["batch"]
+            or workload != "uniform_short" or seed != WORKLOADS["uniform_short"]["seed"]):
+        return None
+    return ATTN_TRAFFIC["bytes_per_launch"]
+
+
 def ssm_traffic(batch):
     import hashlib
     src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "ssm_update.hip")
@@ -392,6 +409,14 @@ def main():
                     if args.state_dtype == "f32" and not spec.conv_kernel else None,
                     "bytes_per_launch": per_launch["ssm"],
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
+    roofline_attention = None
+    if "attention" in kernels:
+        a = kernels["attention"]["GBps"]
+        roofline_attention = {"kernel": "attn_mfma_kernel", "bound": "hbm", "achieved": a,
+                              "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
+                              "traffic": attn_traffic(sc.batch, args.workload, args.seed),
+                              "bytes_per_launch": attn_layer_bytes,
+                              "avg_launch_us": kernels["attention"]["avg_us"]}
 
     # ---- alloc / free churn alone (outside the timed region): host logic + table scatter --
     n_rounds = 200
@@ -457,7 +482,8 @@ def main():
         "algorithmic_bytes_per_step": step_bytes,
         "migrated_pages_per_s": 2 * mig_pages * args.steps / wall,
         "kernels": kernels, "migration_sweep": sweep, "churn": churn, "setup_s": setup_s,
-        "roofline": roofline, "cpu_baseline": base, "parity_sample": parity,
+        "roofline": roofline, "roofline_attention": roofline_attention, "cpu_baseline": base,
+        "parity_sample": parity,
     }
     print(json.dumps(out))
 
