@@ -24,10 +24,14 @@
  *  - AVMP_ERR_DEVICE from avmp_migrate, avmp_alloc_auto or avmp_decode_step means a
  *    HIP call failed after host metadata may already have changed: the pools
  *    object must then be destroyed.  Every other error is a clean no-op.
- *  - avmp_decode_step grows its work buffer on first use and when a larger
- *    batch or handle row arrives (a device synchronisation and an allocation);
- *    with that done and nothing queued, a step only launches kernels and can
- *    be captured in a HIP graph.
+ *  - avmp_decode_step keeps split-K partial results, its run plan and the
+ *    translated slots in a work buffer of the library's.  The buffer is
+ *    allocated on first use (or by avmp_workspace_reserve) for twice the handle
+ *    row in hand and at least 64 pages per request; it only ever grows, by a
+ *    factor of two or more, without waiting for the device, and an outgrown
+ *    buffer stays allocated until the pools are destroyed.  With the buffer in
+ *    place and nothing queued, a step only launches kernels and can be captured
+ *    in a HIP graph.
  *  - not thread-safe: one thread per pools object (the paper's allocator is
  *    single-process).
  *
@@ -215,6 +219,15 @@ int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, vo
  * S <- a*S + dt*x*B[n] in place, y = sum_n S*C[n] with the updated S (before it is
  * rounded to a bf16 block, when the state is stored as bf16). */
 int avmp_decode_step(avmp_pools_t* pools, const avmp_step_t* step, void* stream);
+
+/* Work buffer of avmp_decode_step (its size follows from the number of layers of
+ * each kind, the batch and the handle-row width).  avmp_workspace_reserve sizes it
+ * ahead of time for the largest step the caller will issue, so that no later step
+ * allocates; avmp_workspace_info reports its size in bytes and how many times it
+ * has been allocated so far (either pointer may be NULL). */
+int avmp_workspace_reserve(avmp_pools_t* pools, uint32_t n_attention_layers, uint32_t n_ssm_layers,
+                           uint32_t batch, uint32_t max_pages);
+int avmp_workspace_info(const avmp_pools_t* pools, uint64_t* bytes, uint64_t* allocations);
 
 /* Rebalancing policy of Method, "Dynamic Pool Rebalancing" and Fig. 2.  A
  * four-state machine (BALANCED, KV_PRESSURED / SSM_PRESSURED, REBALANCING) is

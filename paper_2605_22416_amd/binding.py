@@ -129,6 +129,8 @@ lib.avmp_free.argtypes = [_P, _P, C.c_uint32]
 lib.avmp_migrate.argtypes = [_P, C.c_int, C.c_uint32, _P, C.POINTER(avmp_migrate_result_t)]
 lib.avmp_decode_step.argtypes = [_P, C.POINTER(avmp_step_t), _P]
 lib.avmp_flush.argtypes = [_P, _P]
+lib.avmp_workspace_reserve.argtypes = [_P, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
+lib.avmp_workspace_info.argtypes = [_P, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
 lib.avmp_translate.argtypes = [_P, _P, C.c_uint32, _P, _P]
 lib.avmp_resolve.argtypes = [_P, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                              C.POINTER(C.c_uint64)]
@@ -151,7 +153,8 @@ for _f in ("avmp_vmm_arena_create", "avmp_vmm_arena_destroy", "avmp_migrate_by_r
 for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_alloc", "avmp_free",
            "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
            "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read",
-           "avmp_policy_set", "avmp_policy_state", "avmp_alloc_auto"):
+           "avmp_policy_set", "avmp_policy_state", "avmp_alloc_auto", "avmp_workspace_reserve",
+           "avmp_workspace_info"):
     getattr(lib, _f).restype = C.c_int
 
 
@@ -255,6 +258,18 @@ def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles
 
 def avmp_decode_step(pools, step: avmp_step_t, stream=None) -> int:
     return lib.avmp_decode_step(pools, C.byref(step), _stream(stream))
+
+
+def avmp_workspace_reserve(pools, n_attention_layers: int, n_ssm_layers: int, batch: int,
+                           max_pages: int) -> int:
+    return lib.avmp_workspace_reserve(pools, n_attention_layers, n_ssm_layers, batch, max_pages)
+
+
+def avmp_workspace_info(pools):
+    """Returns (rc, bytes, allocations so far)."""
+    nbytes, allocs = C.c_uint64(), C.c_uint64()
+    rc = lib.avmp_workspace_info(pools, C.byref(nbytes), C.byref(allocs))
+    return rc, nbytes.value, allocs.value
 
 
 def avmp_flush(pools, stream=None) -> int:

@@ -94,8 +94,11 @@ struct avmp_pools {
   uint8_t* arena = nullptr;
   uint32_t* table_dev = nullptr;
   unsigned long long* faults_dev = nullptr;
-  float* ws = nullptr;                 // attention chunk partials
+  float* ws = nullptr;                 // work buffer of the decode step (see WorkLayout)
   size_t ws_bytes = 0;
+  uint64_t ws_allocations = 0;
+  std::vector<void*> ws_retired;       // outgrown work buffers: a step in flight (or a captured
+                                       // graph) may still name them, so they live until destroy
   std::vector<avmp::TableUpdate> pending;
   std::vector<uint32_t> pending_zero;  // SSM slots to clear
   Staging staging;
@@ -181,8 +184,8 @@ struct ProfScope {
   avmp_pools* p;
   hipStream_t s;
   int idx = -1;
-  ProfScope(avmp_pools* pools, int kind, hipStream_t stream) : p(pools), s(stream) {
-    if (p->profiling) idx = p->prof_start(kind, s);
+  ProfScope(avmp_pools* pools, bool on, int kind, hipStream_t stream) : p(pools), s(stream) {
+    if (on) idx = p->prof_start(kind, s);
   }
   ~ProfScope() {
     if (idx >= 0) p->prof_stop(idx, s);
@@ -211,7 +214,7 @@ int flush_pending(avmp_pools* p, hipStream_t s) {
   if (upd_bytes) std::memcpy(host, upd.data(), upd_bytes);
   if (zero_bytes) std::memcpy(host + upd_bytes, p->pending_zero.data(), zero_bytes);
   {
-    ProfScope scope(p, AVMP_K_TABLE, s);
+    ProfScope scope(p, p->profiling, AVMP_K_TABLE, s);
     HIP_TRY(avmp::launch_table_updates(p->table_dev,
                                        reinterpret_cast<const avmp::TableUpdate*>(host),
                                        uint32_t(upd.size()), s));
@@ -225,16 +228,221 @@ int flush_pending(avmp_pools* p, hipStream_t s) {
   return AVMP_OK;
 }
 
-int ensure_workspace(avmp_pools* p, size_t bytes) {
-  if (bytes <= p->ws_bytes) return AVMP_OK;
-  if (p->ws) {
-    HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipFree(p->ws));
-    p->ws = nullptr;
-    p->ws_bytes = 0;
+// Where the decode step keeps what is neither input nor output: the fp32 outputs of one
+// layer's short convolution, the split-K partial results of one attention layer, the run
+// plan of the matrix-core path and the pre-translated slots of every attention layer.
+struct WorkLayout {
+  bool mfma = false;
+  uint32_t runs = 0, max_chunks = 0;
+  size_t conv_floats = 0, part_rows = 0, part_floats = 0, prefix_words = 0, plan_words = 0,
+         slot_cap = 0, slot_words = 0;
+  size_t bytes() const {
+    return (conv_floats + part_floats + plan_words + slot_words) * sizeof(float);
   }
-  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->ws), bytes));
+};
+
+WorkLayout work_layout(const avmp_config_t& c, uint32_t n_attn, uint32_t n_ssm, uint32_t batch,
+                       uint32_t max_pages) {
+  WorkLayout L;
+  if (batch == 0) return L;
+  if (n_attn) {
+    L.mfma = avmp::attention_mfma_supported(c.dtype, c.n_q_heads, c.n_kv_heads, c.head_dim);
+    L.runs = avmp::attention_runs_per_head(c.n_kv_heads);
+    const uint32_t worst = (max_pages + avmp::kChunkPages - 1) / avmp::kChunkPages;
+    L.max_chunks = worst < avmp::kMaxChunks ? worst : avmp::kMaxChunks;
+    L.part_rows = L.mfma ? size_t(L.runs) * 2 * c.n_q_heads
+                         : size_t(batch) * L.max_chunks * c.n_q_heads;
+    L.part_floats = (L.part_rows * (size_t(c.head_dim) + 2) + 3) / 4 * 4;   // keeps the plan 16-byte aligned
+    L.prefix_words = (size_t(batch) + 4) / 4 * 4;                           // batch + 1 entries
+    L.plan_words = 4 + L.prefix_words + size_t(L.runs) * 4;
+    L.slot_cap = size_t(batch) * max_pages;                                 // per attention layer
+    L.slot_words = L.mfma ? size_t(n_attn) * L.slot_cap : 0;
+  }
+  if (c.ssm_conv_kernel != 0 && n_ssm) {
+    const size_t conv_dim = size_t(c.ssm_heads) * c.ssm_headdim + 2 * size_t(c.ssm_dstate);
+    L.conv_floats = (size_t(batch) * conv_dim + 3) / 4 * 4;
+  }
+  return L;
+}
+
+// The work buffer only ever grows, by at least a factor of two, and an outgrown buffer is
+// kept until the pools are destroyed: growing neither waits for the device nor takes memory
+// away from a step that is still in flight or recorded in a graph.
+int grow_workspace(avmp_pools* p, size_t bytes) {
+  if (bytes <= p->ws_bytes) return AVMP_OK;
+  if (bytes < 2 * p->ws_bytes) bytes = 2 * p->ws_bytes;
+  void* fresh = nullptr;
+  HIP_TRY(hipMalloc(&fresh, bytes));
+  if (p->ws) p->ws_retired.push_back(p->ws);
+  p->ws = static_cast<float*>(fresh);
   p->ws_bytes = bytes;
+  ++p->ws_allocations;
+  return AVMP_OK;
+}
+
+// Pages per request that a growing work buffer is sized for: twice the row in hand and at
+// least 1024 tokens, so that a decode loop whose handle rows widen page by page allocates
+// once.
+uint32_t roomy_pages(uint32_t max_pages) {
+  const uint64_t twice = 2ull * max_pages;
+  return uint32_t(twice < 64 ? 64 : (twice > 0xFFFFFFFFull ? 0xFFFFFFFFull : twice));
+}
+
+// Argument checks of a decode step; counts the layers of each kind.
+int check_step(avmp_pools* p, const avmp_step_t* st, uint32_t* n_attn_out, uint32_t* n_ssm_out) {
+  if (p == nullptr || st == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, "arena lost its mapping in a failed remap");
+  if (st->n_layers != 0 && st->layer_kind == nullptr) return fail(AVMP_ERR_INVALID_ARG, "layer_kind");
+  uint32_t n_attn = 0, n_ssm = 0;
+  for (uint32_t i = 0; i < st->n_layers; ++i) {
+    if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) ++n_attn;
+    else if (st->layer_kind[i] == AVMP_LAYER_SSM) ++n_ssm;
+    else return fail(AVMP_ERR_INVALID_ARG, "unknown layer kind");
+  }
+  if (st->batch > 65535) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
+  if (n_attn && st->batch &&
+      (!st->kv_handles || !st->ctx || !st->q || !st->o || st->max_pages == 0))
+    return fail(AVMP_ERR_INVALID_ARG, "attention layers need kv_handles, ctx, q, o, max_pages");
+  if ((st->k_new == nullptr) != (st->v_new == nullptr))
+    return fail(AVMP_ERR_INVALID_ARG, "k_new and v_new go together");
+  const bool conv = p->cfg.ssm_conv_kernel != 0;
+  if (n_ssm && st->batch && (!st->ssm_handles || !st->dt || !st->A || !st->y))
+    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need ssm_handles, dt, A, y");
+  if (n_ssm && st->batch && !conv && (!st->x || !st->B || !st->C))
+    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need x, B, C");
+  if (n_ssm && st->batch && conv) {
+    if (!st->xbc || !st->conv_taps || !st->conv_bias)
+      return fail(AVMP_ERR_INVALID_ARG,
+                  "pools with a convolution window need xbc, conv_taps, conv_bias");
+    if ((reinterpret_cast<uintptr_t>(st->xbc) | reinterpret_cast<uintptr_t>(st->conv_taps) |
+         reinterpret_cast<uintptr_t>(st->conv_bias)) & 15u)
+      return fail(AVMP_ERR_INVALID_ARG, "xbc, conv_taps, conv_bias must be 16-byte aligned");
+  }
+  *n_attn_out = n_attn;
+  *n_ssm_out = n_ssm;
+  return AVMP_OK;
+}
+
+// Enqueues the kernels of one decode step.  `ws` is a work buffer of at least L.bytes().
+int run_step(avmp_pools* p, const avmp_step_t* st, hipStream_t s, uint32_t n_attn,
+             const WorkLayout& L, float* ws, bool profile) {
+  const avmp_config_t& c = p->cfg;
+  const size_t eb = c.dtype == AVMP_F32 ? 4 : 2;
+  const bool mfma = L.mfma;
+  const bool append = st->k_new != nullptr;
+  const bool conv = c.ssm_conv_kernel != 0;
+  const size_t conv_dim = size_t(c.ssm_heads) * c.ssm_headdim + 2 * size_t(c.ssm_dstate);
+  float* const conv_out = ws;
+  float* const part_base = ws + L.conv_floats;
+  uint32_t* plan_base = reinterpret_cast<uint32_t*>(part_base + L.part_floats);
+  uint32_t* slots_base = plan_base + L.plan_words;
+  const avmp::DevPools P = p->dev_view();
+  uint32_t ia = 0, is = 0;
+  bool planned = false;
+  for (uint32_t i = 0; i < st->n_layers; ++i) {
+    if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) {
+      avmp::AttnLaunch a{};
+      a.P = P;
+      if (mfma) {
+        a.plan = plan_base;
+        a.prefix = plan_base + 4;
+        a.desc = reinterpret_cast<const uint4*>(plan_base + 4 + L.prefix_words);
+        a.runs = L.runs;
+        a.slots = slots_base + size_t(ia) * L.slot_cap;
+      }
+      a.handles = st->kv_handles + size_t(ia) * st->batch * st->max_pages;
+      a.ctx = st->ctx;
+      const size_t row = size_t(st->batch) * c.n_q_heads * c.head_dim;
+      a.q = static_cast<const char*>(st->q) + size_t(ia) * row * eb;
+      a.o = st->o + size_t(ia) * row;
+      a.part_o = part_base;
+      a.part_ml = part_base + L.part_rows * c.head_dim;
+      a.batch = st->batch;
+      a.max_pages = st->max_pages;
+      a.max_chunks = L.max_chunks;
+      a.n_q_heads = c.n_q_heads;
+      a.n_kv_heads = c.n_kv_heads;
+      a.head_dim = c.head_dim;
+      a.dtype = c.dtype;
+      if (append) {
+        const size_t kvrow = size_t(st->batch) * c.n_kv_heads * c.head_dim * eb;
+        a.append = 1;
+        a.k_new = static_cast<const char*>(st->k_new) + size_t(ia) * kvrow;
+        a.v_new = static_cast<const char*>(st->v_new) + size_t(ia) * kvrow;
+        ProfScope scope(p, profile, AVMP_K_TABLE, s);
+        HIP_TRY(avmp::launch_kv_append(a, s));
+      }
+      if (mfma && !planned) {            // context lengths are the same for every layer
+        ProfScope scope(p, profile, AVMP_K_TABLE, s);
+        HIP_TRY(avmp::launch_attention_plan(a, s));
+        HIP_TRY(avmp::launch_attention_translate(a, st->kv_handles, n_attn, slots_base, s));
+        planned = true;
+      }
+      {
+        ProfScope scope(p, profile, AVMP_K_ATTENTION, s);
+        HIP_TRY(avmp::launch_attention(a, s));
+      }
+      {
+        ProfScope scope(p, profile, AVMP_K_ATTENTION_MERGE, s);
+        HIP_TRY(avmp::launch_attention_merge(a, s));
+      }
+      ++ia;
+    } else {
+      avmp::SsmLaunch a{};
+      a.P = P;
+      a.handles = st->ssm_handles + size_t(is) * st->batch;
+      const size_t xrow = size_t(st->batch) * c.ssm_heads * c.ssm_headdim;
+      if (!conv) {
+        a.x = static_cast<const char*>(st->x) + size_t(is) * xrow * eb;
+        a.B = static_cast<const char*>(st->B) + size_t(is) * st->batch * c.ssm_dstate * eb;
+        a.C = static_cast<const char*>(st->C) + size_t(is) * st->batch * c.ssm_dstate * eb;
+      }
+      a.dt = st->dt + size_t(is) * st->batch * c.ssm_heads;
+      a.A = st->A + size_t(is) * c.ssm_heads;
+      a.y = st->y + size_t(is) * xrow;
+      a.batch = st->batch;
+      a.heads = c.ssm_heads;
+      a.headdim = c.ssm_headdim;
+      a.dstate = c.ssm_dstate;
+      a.dtype = c.dtype;
+      a.state_dtype = c.ssm_state_dtype;
+      if (conv) {
+        // x, B and C of this layer come out of the convolution, as fp32
+        avmp::ConvLaunch cv{};
+        cv.P = P;
+        cv.handles = a.handles;
+        cv.u = static_cast<const char*>(st->xbc) + size_t(is) * st->batch * conv_dim * eb;
+        cv.taps = static_cast<const char*>(st->conv_taps) + size_t(is) * c.ssm_conv_kernel * conv_dim * eb;
+        cv.bias = static_cast<const char*>(st->conv_bias) + size_t(is) * conv_dim * eb;
+        cv.x = conv_out;
+        cv.B = conv_out + xrow;
+        cv.C = cv.B + size_t(st->batch) * c.ssm_dstate;
+        cv.state_bytes = uint64_t(c.ssm_heads) * c.ssm_headdim * c.ssm_dstate *
+                         (c.ssm_state_dtype == AVMP_F32 ? 4 : 2);
+        cv.batch = st->batch;
+        cv.heads = c.ssm_heads;
+        cv.headdim = c.ssm_headdim;
+        cv.dstate = c.ssm_dstate;
+        cv.conv_dim = uint32_t(conv_dim);
+        cv.taps_k = c.ssm_conv_kernel;
+        cv.dtype = c.dtype;
+        {
+          ProfScope scope(p, profile, AVMP_K_CONV, s);
+          HIP_TRY(avmp::launch_conv_update(cv, s));
+        }
+        a.x = cv.x;
+        a.B = cv.B;
+        a.C = cv.C;
+        a.dtype = AVMP_F32;
+      }
+      {
+        ProfScope scope(p, profile, AVMP_K_SSM, s);
+        HIP_TRY(avmp::launch_ssm(a, s));
+      }
+      ++is;
+    }
+  }
   return AVMP_OK;
 }
 
@@ -306,6 +514,7 @@ int avmp_pools_destroy(avmp_pools_t* p) {
         (void)hipEventDestroy(r.b);
       }
     if (p->ws) (void)hipFree(p->ws);
+    for (void* old : p->ws_retired) (void)hipFree(old);
     (void)hipFree(p->table_dev);
     (void)hipFree(p->faults_dev);
   }
@@ -426,7 +635,7 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
     std::memcpy(b->host, moves.data(), bytes);
     // capacities in the view are already the new ones; the copy needs none of them
     {
-      ProfScope scope(p, AVMP_K_MIGRATE_COPY, s);
+      ProfScope scope(p, p->profiling, AVMP_K_MIGRATE_COPY, s);
       HIP_TRY(avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor,
                                         static_cast<const avmp::Move*>(b->host),
                                         uint32_t(moves.size()), s));
@@ -492,173 +701,34 @@ int avmp_migrate_by_remap(avmp_pools_t* p, avmp_vmm_arena_t* a) {
 }
 
 int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
-  if (p == nullptr || st == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
-  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
-  if (p->dead) return fail(AVMP_ERR_DEVICE, "arena lost its mapping in a failed remap");
-  if (st->n_layers != 0 && st->layer_kind == nullptr) return fail(AVMP_ERR_INVALID_ARG, "layer_kind");
   uint32_t n_attn = 0, n_ssm = 0;
-  for (uint32_t i = 0; i < st->n_layers; ++i) {
-    if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) ++n_attn;
-    else if (st->layer_kind[i] == AVMP_LAYER_SSM) ++n_ssm;
-    else return fail(AVMP_ERR_INVALID_ARG, "unknown layer kind");
-  }
-  if (st->batch > 65535) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
-  if (n_attn && st->batch &&
-      (!st->kv_handles || !st->ctx || !st->q || !st->o || st->max_pages == 0))
-    return fail(AVMP_ERR_INVALID_ARG, "attention layers need kv_handles, ctx, q, o, max_pages");
-  if ((st->k_new == nullptr) != (st->v_new == nullptr))
-    return fail(AVMP_ERR_INVALID_ARG, "k_new and v_new go together");
-  const bool append = st->k_new != nullptr;
-  const bool conv = p->cfg.ssm_conv_kernel != 0;
-  if (n_ssm && st->batch && (!st->ssm_handles || !st->dt || !st->A || !st->y))
-    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need ssm_handles, dt, A, y");
-  if (n_ssm && st->batch && !conv && (!st->x || !st->B || !st->C))
-    return fail(AVMP_ERR_INVALID_ARG, "SSM layers need x, B, C");
-  if (n_ssm && st->batch && conv) {
-    if (!st->xbc || !st->conv_taps || !st->conv_bias)
-      return fail(AVMP_ERR_INVALID_ARG,
-                  "pools with a convolution window need xbc, conv_taps, conv_bias");
-    if ((reinterpret_cast<uintptr_t>(st->xbc) | reinterpret_cast<uintptr_t>(st->conv_taps) |
-         reinterpret_cast<uintptr_t>(st->conv_bias)) & 15u)
-      return fail(AVMP_ERR_INVALID_ARG, "xbc, conv_taps, conv_bias must be 16-byte aligned");
-  }
+  int rc = check_step(p, st, &n_attn, &n_ssm);
+  if (rc != AVMP_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int rc = flush_pending(p, s);
+  rc = flush_pending(p, s);
   if (rc != AVMP_OK) return rc;
   if (st->batch == 0) return AVMP_OK;
-
-  const avmp_config_t& c = p->cfg;
-  const size_t eb = c.dtype == AVMP_F32 ? 4 : 2;
-  // work buffer: split-K partial results, plus the run plan of the matrix-core path
-  const bool mfma = avmp::attention_mfma_supported(c.dtype, c.n_q_heads, c.n_kv_heads, c.head_dim);
-  const uint32_t runs = avmp::attention_runs_per_head(c.n_kv_heads);
-  const uint32_t worst = (st->max_pages + avmp::kChunkPages - 1) / avmp::kChunkPages;
-  const uint32_t max_chunks = worst < avmp::kMaxChunks ? worst : avmp::kMaxChunks;
-  const size_t part_rows = mfma ? size_t(runs) * 2 * c.n_q_heads
-                                : size_t(st->batch) * max_chunks * c.n_q_heads;
-  const size_t part_floats = (part_rows * (size_t(c.head_dim) + 2) + 3) / 4 * 4;   // keeps the plan 16-byte aligned
-  const size_t prefix_words = (size_t(st->batch) + 4) / 4 * 4;             // batch + 1 entries
-  const size_t plan_words = 4 + prefix_words + size_t(runs) * 4;
-  const size_t slot_cap = size_t(st->batch) * st->max_pages;           // per attention layer
-  const size_t slot_words = mfma ? size_t(n_attn) * slot_cap : 0;
-  // ... and, in front of them, the fp32 outputs of the short convolution of one layer
-  const size_t conv_dim = size_t(c.ssm_heads) * c.ssm_headdim + 2 * size_t(c.ssm_dstate);
-  const size_t conv_floats = (conv && n_ssm) ? (size_t(st->batch) * conv_dim + 3) / 4 * 4 : 0;
-  if (n_attn || conv_floats) {
-    const size_t attn_words = n_attn ? part_floats + plan_words + slot_words : 0;
-    rc = ensure_workspace(p, (conv_floats + attn_words) * sizeof(float));
+  const WorkLayout L = work_layout(p->cfg, n_attn, n_ssm, st->batch, st->max_pages);
+  if (L.bytes() > p->ws_bytes) {
+    const WorkLayout roomy = work_layout(p->cfg, n_attn, n_ssm, st->batch, roomy_pages(st->max_pages));
+    rc = grow_workspace(p, roomy.bytes());
     if (rc != AVMP_OK) return rc;
   }
-  float* const conv_out = p->ws;
-  float* const part_base = p->ws + conv_floats;
-  uint32_t* plan_base = reinterpret_cast<uint32_t*>(part_base + part_floats);
-  uint32_t* slots_base = plan_base + plan_words;
-  const avmp::DevPools P = p->dev_view();
-  uint32_t ia = 0, is = 0;
-  bool planned = false;
-  for (uint32_t i = 0; i < st->n_layers; ++i) {
-    if (st->layer_kind[i] == AVMP_LAYER_ATTENTION) {
-      avmp::AttnLaunch a{};
-      a.P = P;
-      if (mfma) {
-        a.plan = plan_base;
-        a.prefix = plan_base + 4;
-        a.desc = reinterpret_cast<const uint4*>(plan_base + 4 + prefix_words);
-        a.runs = runs;
-        a.slots = slots_base + size_t(ia) * slot_cap;
-      }
-      a.handles = st->kv_handles + size_t(ia) * st->batch * st->max_pages;
-      a.ctx = st->ctx;
-      const size_t row = size_t(st->batch) * c.n_q_heads * c.head_dim;
-      a.q = static_cast<const char*>(st->q) + size_t(ia) * row * eb;
-      a.o = st->o + size_t(ia) * row;
-      a.part_o = part_base;
-      a.part_ml = part_base + part_rows * c.head_dim;
-      a.batch = st->batch;
-      a.max_pages = st->max_pages;
-      a.max_chunks = max_chunks;
-      a.n_q_heads = c.n_q_heads;
-      a.n_kv_heads = c.n_kv_heads;
-      a.head_dim = c.head_dim;
-      a.dtype = c.dtype;
-      if (append) {
-        const size_t kvrow = size_t(st->batch) * c.n_kv_heads * c.head_dim * eb;
-        a.append = 1;
-        a.k_new = static_cast<const char*>(st->k_new) + size_t(ia) * kvrow;
-        a.v_new = static_cast<const char*>(st->v_new) + size_t(ia) * kvrow;
-        ProfScope scope(p, AVMP_K_TABLE, s);
-        HIP_TRY(avmp::launch_kv_append(a, s));
-      }
-      if (mfma && !planned) {            // context lengths are the same for every layer
-        ProfScope scope(p, AVMP_K_TABLE, s);
-        HIP_TRY(avmp::launch_attention_plan(a, s));
-        HIP_TRY(avmp::launch_attention_translate(a, st->kv_handles, n_attn, slots_base, s));
-        planned = true;
-      }
-      {
-        ProfScope scope(p, AVMP_K_ATTENTION, s);
-        HIP_TRY(avmp::launch_attention(a, s));
-      }
-      {
-        ProfScope scope(p, AVMP_K_ATTENTION_MERGE, s);
-        HIP_TRY(avmp::launch_attention_merge(a, s));
-      }
-      ++ia;
-    } else {
-      avmp::SsmLaunch a{};
-      a.P = P;
-      a.handles = st->ssm_handles + size_t(is) * st->batch;
-      const size_t xrow = size_t(st->batch) * c.ssm_heads * c.ssm_headdim;
-      if (!conv) {
-        a.x = static_cast<const char*>(st->x) + size_t(is) * xrow * eb;
-        a.B = static_cast<const char*>(st->B) + size_t(is) * st->batch * c.ssm_dstate * eb;
-        a.C = static_cast<const char*>(st->C) + size_t(is) * st->batch * c.ssm_dstate * eb;
-      }
-      a.dt = st->dt + size_t(is) * st->batch * c.ssm_heads;
-      a.A = st->A + size_t(is) * c.ssm_heads;
-      a.y = st->y + size_t(is) * xrow;
-      a.batch = st->batch;
-      a.heads = c.ssm_heads;
-      a.headdim = c.ssm_headdim;
-      a.dstate = c.ssm_dstate;
-      a.dtype = c.dtype;
-      a.state_dtype = c.ssm_state_dtype;
-      if (conv) {
-        // x, B and C of this layer come out of the convolution, as fp32
-        avmp::ConvLaunch cv{};
-        cv.P = P;
-        cv.handles = a.handles;
-        cv.u = static_cast<const char*>(st->xbc) + size_t(is) * st->batch * conv_dim * eb;
-        cv.taps = static_cast<const char*>(st->conv_taps) + size_t(is) * c.ssm_conv_kernel * conv_dim * eb;
-        cv.bias = static_cast<const char*>(st->conv_bias) + size_t(is) * conv_dim * eb;
-        cv.x = conv_out;
-        cv.B = conv_out + xrow;
-        cv.C = cv.B + size_t(st->batch) * c.ssm_dstate;
-        cv.state_bytes = uint64_t(c.ssm_heads) * c.ssm_headdim * c.ssm_dstate *
-                         (c.ssm_state_dtype == AVMP_F32 ? 4 : 2);
-        cv.batch = st->batch;
-        cv.heads = c.ssm_heads;
-        cv.headdim = c.ssm_headdim;
-        cv.dstate = c.ssm_dstate;
-        cv.conv_dim = uint32_t(conv_dim);
-        cv.taps_k = c.ssm_conv_kernel;
-        cv.dtype = c.dtype;
-        {
-          ProfScope scope(p, AVMP_K_CONV, s);
-          HIP_TRY(avmp::launch_conv_update(cv, s));
-        }
-        a.x = cv.x;
-        a.B = cv.B;
-        a.C = cv.C;
-        a.dtype = AVMP_F32;
-      }
-      {
-        ProfScope scope(p, AVMP_K_SSM, s);
-        HIP_TRY(avmp::launch_ssm(a, s));
-      }
-      ++is;
-    }
-  }
+  return run_step(p, st, s, n_attn, L, p->ws, p->profiling);
+}
+
+int avmp_workspace_reserve(avmp_pools_t* p, uint32_t n_attention_layers, uint32_t n_ssm_layers,
+                           uint32_t batch, uint32_t max_pages) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  if (batch > 65535) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
+  return grow_workspace(p, work_layout(p->cfg, n_attention_layers, n_ssm_layers, batch, max_pages).bytes());
+}
+
+int avmp_workspace_info(const avmp_pools_t* p, uint64_t* bytes, uint64_t* allocations) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  if (bytes) *bytes = p->ws_bytes;
+  if (allocations) *allocations = p->ws_allocations;
   return AVMP_OK;
 }
 

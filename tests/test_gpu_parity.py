@@ -427,6 +427,47 @@ def test_decode_loop_with_kv_append_and_page_allocation(dtype):
     g.close()
 
 
+def test_decode_loop_with_widening_handle_rows_allocates_the_work_buffer_once():
+    """64 appended tokens, the handle row widened page by page as the longest request
+    grows: the work buffer is allocated by the first step and never again (no step
+    waits for the device or allocates), and every step still matches the oracle."""
+    from paper_2605_22416_amd import binding as av
+    base = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    spec = inputs.ModelSpec("widen", "bf16", 16, base.n_q_heads, base.n_kv_heads, base.head_dim,
+                            8, 16, 32, (inputs.SSM, inputs.ATTN), base.scale_inputs)
+    ctx0 = [0, 100, 255]
+    sc = inputs.make_scenario(spec, "uniform_short", len(ctx0), seed=62, ctx=ctx0, headroom=4.0)
+    op, g, kv, ssm = _both(sc)
+    ctx = np.array(ctx0, dtype=np.uint32)
+    allocations = []
+    for step in range(64):
+        for r in range(len(ctx)):
+            if ctx[r] % 16 == 0:
+                if ctx[r] // 16 >= kv.shape[2]:          # the row is full: one more page slot
+                    kv = np.pad(kv, ((0, 0), (0, 0), (0, 1)), constant_values=0xFFFFFFFF)
+                oc, oh = op.alloc(0, spec.n_attn)
+                lc, lh = av.avmp_alloc(g.p, 0, spec.n_attn)
+                assert oc == lc == orc.OK and list(lh) == oh
+                kv[:, r, ctx[r] // 16] = oh
+        g.kv = kv.copy()
+        g.sc.ctx = ctx.copy()
+        g.sync_handles()
+        inp = inputs.step_inputs(spec, len(ctx), seed=62, step=step)
+        k_new, v_new = inputs.new_token_kv(spec, len(ctx), seed=62, step=step)
+        ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, ctx, inp["q"], ssm, inp["x"], inp["dt"],
+                                      inp["A"], inp["B"], inp["C"], k_new=k_new, v_new=v_new)
+        o, y = g.step(inp, k_new=k_new, v_new=v_new)
+        _check_outputs(spec, o, y, ref_o, ref_y, "widening step %d" % step)
+        allocations.append(av.avmp_workspace_info(g.p)[2])
+        ctx += 1
+    assert kv.shape[2] == 20 and allocations[0] == 1 and allocations[-1] == 1, allocations
+    # a reservation for a larger step allocates once more, and that step then does not
+    assert av.avmp_workspace_reserve(g.p, spec.n_attn, spec.n_ssm, 64, 4096) == av.AVMP_OK
+    rc, nbytes, n = av.avmp_workspace_info(g.p)
+    assert n == 2 and nbytes >= 64 * 4096 * 4
+    g.close()
+
+
 @pytest.mark.parametrize("dtype,Hq,G,D,H,P,N", [
     ("bf16", 16, 1, 64, 3, 24, 16),     # matrix-core kernel, head_dim 64, query group of 16; small SSM tiles
     ("bf16", 8, 8, 256, 2, 40, 256),    # matrix-core kernel, head_dim 256, no grouping; dstate 256 (64 lanes per row)
