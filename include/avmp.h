@@ -220,6 +220,25 @@ int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, vo
  * rounded to a bf16 block, when the state is stored as bf16). */
 int avmp_decode_step(avmp_pools_t* pools, const avmp_step_t* step, void* stream);
 
+/* avmp_decode_step for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same results as avmp_decode_step, but the work
+ * buffer is a static device array of AVMP_NOALLOC_WORKSPACE_BYTES that each GPU the
+ * library runs on holds from first use until the process ends, and the call
+ * allocates nothing (no device, pinned or event allocation).
+ *  - table updates and zero fills queued by avmp_alloc / avmp_free / avmp_migrate
+ *    must have been pushed with avmp_flush: AVMP_ERR_INVALID_ARG otherwise;
+ *  - a step whose work buffer would exceed the static array (large batch x handle
+ *    row: 4 bytes per attention layer, request and page of row width, plus about
+ *    8.5 MB of partial results at 32 query heads x 128) is refused with
+ *    AVMP_ERR_INVALID_ARG and a message that names both sizes;
+ *  - every call on one GPU uses that GPU's array, whatever the pools object: calls
+ *    that overlap in time on one GPU (different streams) race.  Nothing in the
+ *    array has to survive from one call to the next;
+ *  - per-kernel timing (avmp_profile_enable) does not cover this call. */
+#define AVMP_NOALLOC_WORKSPACE_BYTES (32u << 20)
+int avmp_decode_step_noalloc(avmp_pools_t* pools, const avmp_step_t* step, void* stream);
+
 /* Work buffer of avmp_decode_step (its size follows from the number of layers of
  * each kind, the batch and the handle-row width).  avmp_workspace_reserve sizes it
  * ahead of time for the largest step the caller will issue, so that no later step

@@ -128,6 +128,7 @@ lib.avmp_alloc.argtypes = [_P, C.c_int, C.c_uint32, _P]
 lib.avmp_free.argtypes = [_P, _P, C.c_uint32]
 lib.avmp_migrate.argtypes = [_P, C.c_int, C.c_uint32, _P, C.POINTER(avmp_migrate_result_t)]
 lib.avmp_decode_step.argtypes = [_P, C.POINTER(avmp_step_t), _P]
+lib.avmp_decode_step_noalloc.argtypes = [_P, C.POINTER(avmp_step_t), _P]
 lib.avmp_flush.argtypes = [_P, _P]
 lib.avmp_workspace_reserve.argtypes = [_P, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
 lib.avmp_workspace_info.argtypes = [_P, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
@@ -154,7 +155,7 @@ for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_all
            "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
            "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read",
            "avmp_policy_set", "avmp_policy_state", "avmp_alloc_auto", "avmp_workspace_reserve",
-           "avmp_workspace_info"):
+           "avmp_workspace_info", "avmp_decode_step_noalloc"):
     getattr(lib, _f).restype = C.c_int
 
 
@@ -258,6 +259,13 @@ def make_step(batch: int, layer_kinds: Sequence[int], max_pages: int, kv_handles
 
 def avmp_decode_step(pools, step: avmp_step_t, stream=None) -> int:
     return lib.avmp_decode_step(pools, C.byref(step), _stream(stream))
+
+
+AVMP_NOALLOC_WORKSPACE_BYTES = 32 << 20
+
+
+def avmp_decode_step_noalloc(pools, step: avmp_step_t, stream=None) -> int:
+    return lib.avmp_decode_step_noalloc(pools, C.byref(step), _stream(stream))
 
 
 def avmp_workspace_reserve(pools, n_attention_layers: int, n_ssm_layers: int, batch: int,

@@ -81,6 +81,42 @@ struct Staging {
   }
 };
 
+// Work buffer of avmp_decode_step_noalloc: one array per GPU, alive for the whole process.
+// In host code its name is only a stand-in for the symbol; the memory's address on a
+// device comes from hipGetSymbolAddress with that device current (scratch_on_device).
+constexpr size_t kScratchBytes = size_t(AVMP_NOALLOC_WORKSPACE_BYTES);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on device `dev` (looked up once per device); nullptr on failure,
+// with the reason in *err.
+void* scratch_on_device(int dev, hipError_t* err) {
+  *err = hipSuccess;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  if (g_scratch_ptr[dev] != nullptr) return g_scratch_ptr[dev];
+  int current = -1;
+  *err = hipGetDevice(&current);
+  if (*err != hipSuccess) return nullptr;
+  if (current != dev) {
+    *err = hipSetDevice(dev);
+    if (*err != hipSuccess) return nullptr;
+  }
+  void* ptr = nullptr;
+  *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (current != dev) {
+    const hipError_t back = hipSetDevice(current);
+    if (*err == hipSuccess) *err = back;
+  }
+  if (*err != hipSuccess) return nullptr;
+  g_scratch_ptr[dev] = ptr;
+  return ptr;
+}
+
 }  // namespace
 
 struct avmp_vmm_arena {
@@ -91,6 +127,7 @@ struct avmp_pools {
   avmp_config_t cfg{};
   avmp::PoolState st;
   bool has_device = false;
+  int device = -1;                     // the GPU the arena lives on
   uint8_t* arena = nullptr;
   uint32_t* table_dev = nullptr;
   unsigned long long* faults_dev = nullptr;
@@ -486,7 +523,24 @@ int avmp_pools_create(const avmp_config_t* cfg, void* arena_dev, size_t arena_by
   if (arena_dev != nullptr) {
     p->arena = static_cast<uint8_t*>(arena_dev);
     const size_t entries = size_t(p->st.max_vid(0)) + p->st.max_vid(1);
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p->table_dev), entries * sizeof(uint32_t));
+    // the GPU that holds the arena, and that GPU's copy of the static work buffer
+    hipPointerAttribute_t attr{};
+    hipError_t e = hipPointerGetAttributes(&attr, arena_dev);
+    int current = -1;
+    if (e == hipSuccess) {
+      p->device = attr.device;
+      e = hipGetDevice(&current);
+    } else {
+      (void)hipGetLastError();          // memory HIP does not track (a VA reservation): current device
+      e = hipGetDevice(&current);
+      p->device = current;
+    }
+    if (e == hipSuccess && current != p->device) {
+      delete p;
+      return fail(AVMP_ERR_INVALID_ARG, "the arena's GPU must be the current device");
+    }
+    if (e == hipSuccess) (void)scratch_on_device(p->device, &e);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->table_dev), entries * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemset(p->table_dev, 0xFF, entries * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->faults_dev), sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(p->faults_dev, 0, sizeof(unsigned long long));
@@ -715,6 +769,30 @@ int avmp_decode_step(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
     if (rc != AVMP_OK) return rc;
   }
   return run_step(p, st, s, n_attn, L, p->ws, p->profiling);
+}
+
+int avmp_decode_step_noalloc(avmp_pools_t* p, const avmp_step_t* st, void* stream) {
+  uint32_t n_attn = 0, n_ssm = 0;
+  const int rc = check_step(p, st, &n_attn, &n_ssm);
+  if (rc != AVMP_OK) return rc;
+  // pushing queued table updates takes pinned staging memory and events: not in this call
+  if (!p->pending.empty() || !p->pending_zero.empty())
+    return fail(AVMP_ERR_INVALID_ARG,
+                "table updates or zero fills are queued: call avmp_flush before avmp_decode_step_noalloc");
+  if (st->batch == 0) return AVMP_OK;
+  const WorkLayout L = work_layout(p->cfg, n_attn, n_ssm, st->batch, st->max_pages);
+  if (L.bytes() > kScratchBytes) {
+    char msg[160];
+    std::snprintf(msg, sizeof msg,
+                  "this step needs a work buffer of %zu bytes; the static one holds %zu "
+                  "(AVMP_NOALLOC_WORKSPACE_BYTES)", L.bytes(), kScratchBytes);
+    return fail(AVMP_ERR_INVALID_ARG, msg);
+  }
+  hipError_t e = hipSuccess;
+  void* ws = scratch_on_device(p->device, &e);
+  if (ws == nullptr) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+  // no per-kernel event pairs here: creating events allocates
+  return run_step(p, st, static_cast<hipStream_t>(stream), n_attn, L, static_cast<float*>(ws), false);
 }
 
 int avmp_workspace_reserve(avmp_pools_t* p, uint32_t n_attention_layers, uint32_t n_ssm_layers,
