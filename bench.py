@@ -217,7 +217,7 @@ def main():
     import numpy as np
     import torch
     from paper_2605_22416_amd import binding as av
-    from paper_2605_22416_amd import inputs
+    from gen import inputs
     from paper_2605_22416_amd.session import DeviceSession
 
     if not torch.cuda.is_available():

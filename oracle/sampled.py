@@ -11,7 +11,7 @@ from __future__ import annotations
 import numpy as np
 
 from oracle import avmp_oracle as orc
-from paper_2605_22416_amd import inputs
+from gen import inputs
 
 
 def oracle_shape(spec) -> orc.Shape:

@@ -11,7 +11,7 @@ import numpy as np
 import torch
 
 from . import binding as av
-from . import inputs
+from gen import inputs
 
 DEV = "cuda:0"
 

@@ -23,7 +23,7 @@ from typing import Dict, List
 import numpy as np
 
 from . import binding as av
-from . import inputs
+from gen import inputs
 
 
 def _prompt_lengths(workload: str, rng: np.random.Generator, n: int) -> np.ndarray:

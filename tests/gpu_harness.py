@@ -2,7 +2,7 @@
 it the same bytes the oracle gets."""
 import numpy as np
 
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from paper_2605_22416_amd.session import DEV, DeviceSession, to_dev  # noqa: F401
 from tests import helpers
 

@@ -9,7 +9,7 @@ import pytest
 
 from oracle import avmp_oracle as orc
 from oracle.sampled import RequestReference
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from tests import helpers
 
 pytestmark = pytest.mark.gpu

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import avmp_oracle as orc
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from tests import helpers
 
 pytestmark = pytest.mark.gpu

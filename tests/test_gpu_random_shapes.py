@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import avmp_oracle as orc
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from tests import helpers
 from tests.test_gpu_parity import _both, _check_outputs, _check_states, _check_translation
 

@@ -9,7 +9,7 @@ import pytest
 
 from oracle import avmp_oracle as orc
 from paper_2605_22416_amd import binding as av
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from tests import helpers
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))

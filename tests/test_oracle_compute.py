@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from oracle import avmp_oracle as orc
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from tests import helpers
 
 

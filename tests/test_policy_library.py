@@ -6,7 +6,7 @@ import pytest
 
 from oracle import avmp_oracle as orc
 from paper_2605_22416_amd import binding as av
-from paper_2605_22416_amd import inputs
+from gen import inputs
 from tests import helpers
 
 

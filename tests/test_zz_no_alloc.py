@@ -5,7 +5,7 @@ and states), on two calls in a row, the second with a smaller input."""
 import numpy as np
 import pytest
 
-from paper_2605_22416_amd import inputs
+from gen import inputs
 
 pytestmark = pytest.mark.gpu
 
