@@ -411,12 +411,24 @@ def main():
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
     roofline_attention = None
     if "attention" in kernels:
-        a = kernels["attention"]["GBps"]
-        roofline_attention = {"kernel": "attn_mfma_kernel", "bound": "hbm", "achieved": a,
+        # everything an attention layer launches: the attention kernel (which merges its own
+        # partial results), the separate merge where the vector-ALU path runs, and the layer's
+        # share of the once-per-step preparation (run plan + translation of all KV handles)
+        parts = {"attention": kernels["attention"]["avg_us"]}
+        if "attention_merge" in kernels:
+            parts["attention_merge"] = kernels["attention_merge"]["avg_us"]
+        if "attention_prepare" in kernels:
+            parts["attention_prepare_share"] = (kernels["attention_prepare"]["avg_us"]
+                                                * kernels["attention_prepare"]["launches"]
+                                                / kernels["attention"]["launches"])
+        layer_us = sum(parts.values())
+        a = attn_layer_bytes / (layer_us * 1e-6) / 1e9
+        roofline_attention = {"kernel": "attn_mfma_kernel + attn_prepare_kernel / attention layers",
+                              "bound": "hbm", "achieved": a,
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
                               "traffic": attn_traffic(sc.batch, args.workload, args.seed),
                               "bytes_per_launch": attn_layer_bytes,
-                              "avg_launch_us": kernels["attention"]["avg_us"]}
+                              "avg_layer_us": layer_us, "avg_us_by_kernel": parts}
 
     # ---- alloc / free churn alone (outside the timed region): host logic + table scatter --
     n_rounds = 200

@@ -145,8 +145,8 @@ typedef struct avmp_step {
   const avmp_handle_t* kv_handles;   /* device [n_attn][batch][max_pages]; entries at or beyond
                                         ceil(ctx/16) are ignored */
   const uint32_t* ctx;               /* device [batch] tokens resident per request (may be 0) */
-  const void* q;                     /* device [n_attn][batch][n_q_heads][head_dim] elements */
-  float* o;                          /* device [n_attn][batch][n_q_heads][head_dim] fp32 out */
+  const void* q;                     /* device [n_attn][batch][n_q_heads][head_dim] elements, 16-byte aligned */
+  float* o;                          /* device [n_attn][batch][n_q_heads][head_dim] fp32 out, 16-byte aligned */
   const avmp_handle_t* ssm_handles;  /* device [n_ssm][batch] */
   const void* x;                     /* device [n_ssm][batch][H][P] elements */
   const float* dt;                   /* device [n_ssm][batch][H] fp32, already positive */
@@ -315,12 +315,13 @@ int avmp_device_faults(avmp_pools_t* pools, void* stream, uint64_t* out);
  * kernel kind since the last read, writes them to *out and resets them. */
 enum {
   AVMP_K_ATTENTION = 0,        /* paged GQA decode attention (per layer) */
-  AVMP_K_ATTENTION_MERGE = 1,  /* merge of per-chunk partial results (per layer) */
+  AVMP_K_ATTENTION_MERGE = 1,  /* merge of split-K partial results (per layer) */
   AVMP_K_SSM = 2,              /* SSM state update (per layer) */
   AVMP_K_MIGRATE_COPY = 3,     /* migration copy + remap */
   AVMP_K_TABLE = 4,            /* table scatter + zero fill of new SSM blocks */
   AVMP_K_CONV = 5,             /* short convolution in front of the recurrence (per layer) */
-  AVMP_K_COUNT = 6
+  AVMP_K_ATTENTION_PREPARE = 6,/* run plan + translation of all KV handles (once per step) */
+  AVMP_K_COUNT = 7
 };
 typedef struct avmp_profile {
   double ms[AVMP_K_COUNT];

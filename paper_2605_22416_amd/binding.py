@@ -95,9 +95,10 @@ class avmp_step_t(C.Structure):
 
 
 (AVMP_K_ATTENTION, AVMP_K_ATTENTION_MERGE, AVMP_K_SSM, AVMP_K_MIGRATE_COPY, AVMP_K_TABLE,
- AVMP_K_CONV) = range(6)
-AVMP_K_COUNT = 6
-KERNEL_NAMES = ("attention", "attention_merge", "ssm", "migrate_copy", "table", "conv")
+ AVMP_K_CONV, AVMP_K_ATTENTION_PREPARE) = range(7)
+AVMP_K_COUNT = 7
+KERNEL_NAMES = ("attention", "attention_merge", "ssm", "migrate_copy", "table", "conv",
+                "attention_prepare")
 
 
 class avmp_profile_t(C.Structure):

@@ -7,11 +7,23 @@
 // (a page costs one, starting a request a few) and wavefront w walks run w,
 // crossing request boundaries as it goes.  A run that covers a whole request
 // writes the output row; otherwise it leaves a partial result (un-normalised
-// sum, running max, running sum) that the merge kernel combines in logical
-// order.  Every wavefront does about the same work, so the launch has no tail,
-// and the split is a function of the context lengths alone: physical placement
-// and migration cannot change one bit of the result.  A one-block plan kernel
-// computes the page prefix sums and each run's stretch once per decode step.
+// sum, running max, running sum) that the merge kernel combines in logical (run)
+// order, one wavefront per (request, KV head).  Every wavefront does about the same
+// work, so the launch has no tail, and the split is a function of the context
+// lengths alone: physical placement and migration cannot change one bit of the
+// result.  One preparation kernel per decode step holds a plan block (page prefix
+// sums, each run's stretch) and, beside it, the blocks that translate every KV
+// handle of every attention layer to its slot.
+//
+// Why the merge is a launch of its own.  Letting the wavefront that completes a
+// request (an arrival counter per request) merge inside the attention kernel was
+// built and measured at the Jamba-shaped batch of 64: with device-scope fences around
+// the counter the launch went from 46 to 165 us (on this chip such a fence writes
+// back and invalidates a whole L2, and 2048 wavefronts do it at once); with
+// device-scope loads and stores for the partial results and no fence, 59 us, against
+// 46 + 4 us for the two launches.  All wavefronts end together, so the write-through
+// stores, the counter round trip and the merge loads pile up at the end of the
+// launch where nothing overlaps them.
 //
 // The in-page layout is the matrix-core operand order, so operands go from
 // global memory to registers to MFMA with no LDS staging and no conversion:
@@ -75,25 +87,42 @@ constexpr uint32_t kMinRunPages = 4;
 // that waits on the request index, the refill of the page pipeline, the output row.
 constexpr uint32_t kRequestCost = 5;
 
-// One block: page prefix sums over the batch and the cut of the batch's pages into
-// runs of equal COST.  Request r costs kRequestCost + its pages; on the cost axis it
-// sits at prefix[r] + kRequestCost * r, its page p at that + kRequestCost + p.  Run w
-// takes the pages whose position falls into [w * cpw, (w + 1) * cpw): as pages they
-// are still one contiguous stretch of the batch's page sequence, so desc[w] =
-// (first request, first page in it, first and one-past-last index in that sequence).
-// plan[0] = total pages, plan[1] = cost per run (cpw).
-__global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restrict__ ctx, uint32_t batch,
-                                                         uint32_t max_pages, uint32_t runs,
-                                                         uint32_t append,
-                                                         uint32_t* __restrict__ plan,
-                                                         uint32_t* __restrict__ prefix,
-                                                         uint4* __restrict__ desc) {
+// Preparation of a decode step's attention layers, one launch.
+//
+// Block 0 is the plan.  It computes the page prefix sums over the batch and cuts the
+// batch's page sequence into runs of equal COST: request r costs kRequestCost + its
+// pages; on the cost axis it sits at prefix[r] + kRequestCost * r, its page p at that
+// + kRequestCost + p.  Run w takes the pages whose position falls into
+// [w * cpw, (w + 1) * cpw): as pages they are still one contiguous stretch of the
+// batch's page sequence, so desc[w] = (first request, first page in it, first and
+// one-past-last index in that sequence).  plan[0] = total pages, plan[1] = cost per
+// run (cpw).  It also writes the zero output rows of requests without resident
+// tokens and counts contexts that exceed the handle row.
+//
+// Every other block translates 256 entries of the handle tables of all attention
+// layers: slots[layer][r][page] = physical slot (0xFFFFFFFF if the handle does not
+// resolve, which is counted).  The table cannot change inside a step, so it is
+// consulted once per page instead of once per page per KV head, and the attention
+// waves read plain slots.  The two parts do not depend on each other.
+struct PrepareArgs {
+  DevPools P;
+  const uint32_t* ctx;        // [batch]
+  const uint32_t* handles;    // [n_attn][batch][max_pages]
+  uint32_t* slots;            // [n_attn][batch][max_pages] out
+  uint32_t* plan;             // [2] out
+  uint32_t* prefix;           // [batch + 1] out
+  uint4* desc;                // [runs] out
+  float* o;                   // [n_attn][batch][n_q_heads * head_dim]: rows of empty requests
+  uint32_t batch, max_pages, runs, append, n_attn, row_floats;
+};
+
+__device__ void plan_block(const PrepareArgs& a) {
   __shared__ uint32_t sums[1024];
-  const uint32_t tid = threadIdx.x;
+  const uint32_t tid = threadIdx.x, batch = a.batch, runs = a.runs;
   const uint32_t seg = (batch + 1023) / 1024;
   const uint32_t lo = min(batch, tid * seg), hi = min(batch, lo + seg);
   uint32_t local = 0;
-  for (uint32_t r = lo; r < hi; ++r) local += pages_of(attended_tokens(ctx, r, append), max_pages);
+  for (uint32_t r = lo; r < hi; ++r) local += pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
   sums[tid] = local;
   __syncthreads();
   for (uint32_t off = 1; off < 1024; off <<= 1) {          // inclusive scan
@@ -104,8 +133,8 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
   }
   uint32_t run = sums[tid] - local;                         // exclusive start of this segment
   for (uint32_t r = lo; r < hi; ++r) {
-    prefix[r] = run;
-    run += pages_of(attended_tokens(ctx, r, append), max_pages);
+    a.prefix[r] = run;
+    run += pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
   }
   const uint32_t total = sums[1023];
   const uint64_t total_cost = uint64_t(total) + uint64_t(kRequestCost) * batch;
@@ -113,9 +142,9 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
   // shorter runs would only add partial results to merge
   const uint64_t cpw = max(uint64_t(kMinRunPages + kRequestCost), (total_cost + runs - 1) / runs);
   if (tid == 0) {
-    prefix[batch] = total;
-    plan[0] = total;
-    plan[1] = uint32_t(cpw);
+    a.prefix[batch] = total;
+    a.plan[0] = total;
+    a.plan[1] = uint32_t(cpw);
   }
   __syncthreads();                                          // prefix[] visible to the block
   // first page at or after cost position c: (request, page in it, index in the page sequence)
@@ -126,44 +155,195 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const uint32_t* __restr
       return total;
     }
     // last r whose cost position prefix[r] + kRequestCost * r is <= c
-    uint32_t a = 0, b = batch;
-    while (b - a > 1) {
-      const uint32_t mid = (a + b) / 2;
-      if (uint64_t(prefix[mid]) + uint64_t(kRequestCost) * mid <= c) a = mid; else b = mid;
+    uint32_t lo_r = 0, hi_r = batch;
+    while (hi_r - lo_r > 1) {
+      const uint32_t mid = (lo_r + hi_r) / 2;
+      if (uint64_t(a.prefix[mid]) + uint64_t(kRequestCost) * mid <= c) lo_r = mid; else hi_r = mid;
     }
-    const uint64_t at = uint64_t(prefix[a]) + uint64_t(kRequestCost) * a + kRequestCost;   // its page 0
-    const uint32_t p = c > at ? uint32_t(c - at) : 0;       // c < position of request a + 1, so p < its pages
-    *rq = a;                                                // (or p = 0 in a request without pages: the
+    const uint64_t at = uint64_t(a.prefix[lo_r]) + uint64_t(kRequestCost) * lo_r + kRequestCost;   // its page 0
+    const uint32_t p = c > at ? uint32_t(c - at) : 0;       // c < position of request lo_r + 1, so p < its pages
+    *rq = lo_r;                                             // (or p = 0 in a request without pages: the
     *pg = p;                                                //  walk skips it)
-    return prefix[a] + p;
+    return a.prefix[lo_r] + p;
   };
   for (uint32_t w = tid; w < runs; w += 1024) {
     uint32_t r0, p0, r1, p1;
     const uint32_t first = first_page_at(uint64_t(w) * cpw, &r0, &p0);
     const uint32_t last = first_page_at(uint64_t(w + 1) * cpw, &r1, &p1);
-    desc[w] = make_uint4(r0, p0, first, last);
+    a.desc[w] = make_uint4(r0, p0, first, last);
+  }
+  // requests without resident tokens get zero rows; a context beyond the handle row is counted
+  __shared__ uint32_t n_empty;
+  uint32_t* const empties = sums;                           // the scan is done with it
+  __syncthreads();
+  if (tid == 0) n_empty = 0;
+  __syncthreads();
+  for (uint32_t r = tid; r < batch; r += 1024) {
+    const uint32_t n = attended_tokens(a.ctx, r, a.append);
+    if (uint64_t(n) > uint64_t(a.max_pages) * 16u)
+      for (uint32_t la = 0; la < a.n_attn; ++la) count_fault(a.P);
+    if (n != 0) continue;
+    const uint32_t at = atomicAdd(&n_empty, 1u);
+    if (at < 1024) {
+      empties[at] = r;
+    } else {                                                // more than the list holds: by this thread alone
+      for (uint32_t la = 0; la < a.n_attn; ++la) {
+        float* rows = a.o + (size_t(la) * batch + r) * a.row_floats;
+        for (uint32_t d = 0; d < a.row_floats; ++d) rows[d] = 0.f;
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t listed = min(n_empty, 1024u);
+  for (uint32_t i = 0; i < listed; ++i) {
+    const uint32_t r = empties[i];
+    for (uint32_t la = 0; la < a.n_attn; ++la) {
+      float* rows = a.o + (size_t(la) * batch + r) * a.row_floats;
+      for (uint32_t d = tid; d < a.row_floats; d += 1024) rows[d] = 0.f;
+    }
   }
 }
 
-// Translation of every KV handle the step will touch, for all attention layers at
-// once: slots[layer][prefix[r] + page] = physical slot (0xFFFFFFFF if the handle does
-// not resolve).  The table cannot change inside a step, so the attention waves read
-// their run's slots as one contiguous load instead of walking handle -> table per
-// page batch, and the table is consulted once per page instead of once per KV head.
-__global__ __launch_bounds__(256) void attn_translate_kernel(DevPools P, const uint32_t* __restrict__ handles,
-                                                             const uint32_t* __restrict__ ctx,
-                                                             const uint32_t* __restrict__ prefix,
-                                                             uint32_t batch, uint32_t max_pages,
-                                                             uint32_t append, uint32_t* __restrict__ slots) {
-  const uint32_t page = blockIdx.x * 256 + threadIdx.x, r = blockIdx.y, la = blockIdx.z;
-  if (page >= pages_of(attended_tokens(ctx, r, append), max_pages)) return;
-  const size_t cap = size_t(batch) * max_pages;
-  const uint32_t h = handles[la * cap + size_t(r) * max_pages + page];
-  const uint64_t off = translate_offset(P, h, 0);
-  uint32_t slot = kDevUnmapped;
-  if (off == ~0ull) count_fault(P);
-  else slot = uint32_t(off / P.unit[0]);
-  slots[la * cap + prefix[r] + page] = slot;
+__global__ __launch_bounds__(1024) void attn_prepare_kernel(PrepareArgs a) {
+  if (blockIdx.x == 0) {
+    plan_block(a);
+    return;
+  }
+  // four entries per thread; a row's entries beyond the request's pages are left as they are
+  const uint64_t per_layer = uint64_t(a.batch) * a.max_pages;
+  const uint64_t entries = per_layer * a.n_attn;
+  for (uint32_t k = 0; k < 4; ++k) {
+    const uint64_t e = (uint64_t(blockIdx.x - 1) * 4 + k) * 1024 + threadIdx.x;
+    if (e >= entries) return;
+    const uint32_t r = uint32_t((e % per_layer) / a.max_pages), page = uint32_t(e % a.max_pages);
+    if (page >= pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages)) continue;
+    const uint64_t off = translate_offset(a.P, a.handles[e], 0);
+    uint32_t slot = kDevUnmapped;
+    if (off == ~0ull) count_fault(a.P);
+    else slot = uint32_t(off / a.P.unit[0]);
+    a.slots[e] = slot;
+  }
+}
+
+// Where run w of KV head g keeps a partial result: a run leaves at most two, slot 1 for
+// the piece that starts its request, slot 0 for the piece that continues one.
+__device__ __forceinline__ size_t partial_slot(uint32_t g, uint32_t runs, uint32_t w, bool starts_request) {
+  return (size_t(g) * runs + w) * 2 + (starts_request ? 1 : 0);
+}
+
+// Combines the np partial results of (request r, KV head g), left by runs wa .. wa + np - 1,
+// into the group's output rows.  One wavefront; the order of every sum depends on np alone.
+//   statistics: lane (piece kk, head i) of a block of 64 / HS pieces holds that piece's running
+//     max and sum; the row maximum M_i and the total L_i come from shuffles across the block;
+//   rows: a partial row is D floats = D / 4 lanes of float4, so one load instruction fetches
+//     64 / (D / 4) rows; lane group `sub` takes the pieces k = sub (mod that many), adds them
+//     up in ascending k, and the groups are added in ascending order at the end.
+// HS = head stride of the statistics layout (4 for query groups up to 4, else 16).
+template <int D, int HS>
+__device__ void merge_pieces(const AttnLaunch& a, uint32_t g, uint32_t r, uint32_t wa, uint32_t np,
+                             uint32_t lane) {
+  constexpr uint32_t LPR = D / 4;            // lanes per partial row
+  constexpr uint32_t RPL = 64 / LPR;         // rows per load instruction: 4, 2 or 1
+  constexpr uint32_t PB = 64 / HS;           // pieces per block of statistics
+  const uint32_t Hq = a.n_q_heads, Gq = Hq / a.n_kv_heads;
+  const uint32_t kk = lane / HS, hi = lane % HS;       // statistics role
+  const uint32_t sub = lane / LPR, c = lane % LPR;     // row role
+  auto row_of = [&](uint32_t k, uint32_t i) -> size_t {
+    return partial_slot(g, a.runs, wa + k, k == 0) * Gq + i;
+  };
+  float M = -INFINITY;                        // row maximum of head hi over all pieces
+  float L = 0.f;                              // this lane's share of the total of head hi
+  float4 acc[HS];
+#pragma unroll
+  for (int i = 0; i < HS; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (np <= PB) {
+    // the usual case, one block of statistics: every load is issued before anything is used
+    float2 ml = make_float2(-INFINITY, 0.f);
+    if (kk < np && hi < Gq) ml = *reinterpret_cast<const float2*>(a.part_ml + row_of(kk, hi) * 2);
+    float4 v[PB / RPL][HS];
+#pragma unroll
+    for (uint32_t t = 0; t < PB / RPL; ++t) {
+      const uint32_t k = t * RPL + sub;
+#pragma unroll
+      for (int i = 0; i < HS; ++i)
+        v[t][i] = (k < np && uint32_t(i) < Gq)
+                      ? *reinterpret_cast<const float4*>(a.part_o + row_of(k, i) * D + 4 * c)
+                      : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    M = ml.x;
+#pragma unroll
+    for (uint32_t o = HS; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, int(o)));
+    const float wgt = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);   // -inf: a piece whose pages were all skipped
+    L = ml.y * wgt;
+#pragma unroll
+    for (uint32_t t = 0; t < PB / RPL; ++t) {
+      const uint32_t k2 = t * RPL + sub;
+#pragma unroll
+      for (int i = 0; i < HS; ++i) {
+        const float w = __shfl(wgt, int(k2 * HS + i));            // 0 where the piece does not exist
+        acc[i].x += w * v[t][i].x;
+        acc[i].y += w * v[t][i].y;
+        acc[i].z += w * v[t][i].z;
+        acc[i].w += w * v[t][i].w;
+      }
+    }
+  } else {
+    for (uint32_t base = 0; base < np; base += PB) {
+      const uint32_t k = base + kk;
+      if (k < np && hi < Gq) M = fmaxf(M, a.part_ml[row_of(k, hi) * 2]);
+    }
+#pragma unroll
+    for (uint32_t o = HS; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, int(o)));
+    for (uint32_t base = 0; base < np; base += PB) {
+      float wgt = 0.f;
+      {
+        const uint32_t k = base + kk;
+        if (k < np && hi < Gq) {
+          const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + row_of(k, hi) * 2);
+          wgt = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);
+          L += ml.y * wgt;
+        }
+      }
+#pragma unroll
+      for (uint32_t t = 0; t < PB / RPL; ++t) {
+        const uint32_t k2 = t * RPL + sub, k = base + k2;    // this lane group's piece of the round
+#pragma unroll
+        for (int i = 0; i < HS; ++i) {
+          const float w = __shfl(wgt, int(k2 * HS + i));
+          if (k < np && uint32_t(i) < Gq) {
+            const float4 v = *reinterpret_cast<const float4*>(a.part_o + row_of(k, i) * D + 4 * c);
+            acc[i].x += w * v.x;
+            acc[i].y += w * v.y;
+            acc[i].z += w * v.z;
+            acc[i].w += w * v.w;
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (uint32_t o = HS; o < 64; o <<= 1) L += __shfl_xor(L, int(o));
+  // lane groups 1 .. RPL-1 hand their sums to group 0, which adds them in ascending order
+#pragma unroll
+  for (int i = 0; i < HS; ++i) {
+    float4 sum = acc[i];
+#pragma unroll
+    for (uint32_t q = 1; q < RPL; ++q) {
+      const int src = int(q * LPR + c);
+      sum.x += __shfl(acc[i].x, src);
+      sum.y += __shfl(acc[i].y, src);
+      sum.z += __shfl(acc[i].z, src);
+      sum.w += __shfl(acc[i].w, src);
+    }
+    const float Li = __shfl(L, i);            // lane i (piece 0 of the block, head i) holds the total
+    if (sub == 0 && uint32_t(i) < Gq) {
+      float* orow = a.o + (size_t(r) * Hq + size_t(g) * Gq + i) * D;
+      const float inv = Li > 0.f ? 1.f / Li : 0.f;
+      *reinterpret_cast<float4*>(orow + 4 * c) =
+          Li > 0.f ? make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv)
+                   : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
 }
 
 // At least two wavefronts per SIMD for head_dim up to 128 (256 registers each).
@@ -179,11 +359,22 @@ void attn_mfma_kernel(AttnLaunch a) {
   const uint64_t item_end = start.w;
   if (item >= item_end) return;
   uint32_t r = start.x, page = start.y;
-  // the run's first 64 slots (for the usual run lengths: all of them), requested before
-  // anything that depends on the context lengths
-  const uint32_t item0 = uint32_t(item);
-  const uint32_t win_n = uint32_t(min(uint64_t(64), item_end - item));
-  const uint32_t my_win = lane < win_n ? a.slots[item0 + lane] : kDevUnmapped;
+  const uint32_t max_pages = a.max_pages;
+  // Slots come 64 at a time, one per lane: lane l of a fetch for (request rr, page bb) holds the
+  // slot of page bb + l.  The fetch for the stretch after the one being walked is always in
+  // flight (the same request's next 64 pages, or the next request's first), and the first is
+  // requested before anything that depends on the context lengths.
+  uint32_t pre_r = 0, pre_base = 0, pre_val = kDevUnmapped;
+  auto fetch_slots = [&](uint32_t rr, uint32_t bb) -> uint32_t {
+    return (rr < a.batch && uint64_t(bb) + lane < max_pages)
+               ? a.slots[size_t(rr) * max_pages + bb + lane] : kDevUnmapped;
+  };
+  auto prefetch_slots = [&](uint32_t rr, uint32_t bb) {
+    pre_r = rr;
+    pre_base = bb;
+    pre_val = fetch_slots(rr, bb);
+  };
+  prefetch_slots(r, page);
   const uint64_t unit_kv = a.P.unit[0];
   const uint32_t G = a.n_kv_heads, Hq = a.n_q_heads, Gq = Hq / G;
   const float scale_log2 = kLog2e / sqrtf(float(D));
@@ -192,7 +383,7 @@ void attn_mfma_kernel(AttnLaunch a) {
 
   while (item < item_end && r < a.batch) {
     const uint32_t n_ctx = attended_tokens(a.ctx, r, a.append);
-    const uint32_t n_pages = pages_of(n_ctx, a.max_pages);
+    const uint32_t n_pages = pages_of(n_ctx, max_pages);
     if (page >= n_pages) {             // request without pages (or exhausted): next one
       ++r;
       page = 0;
@@ -201,6 +392,7 @@ void attn_mfma_kernel(AttnLaunch a) {
     const uint32_t n_tok = min(n_ctx, n_pages * 16u);
     const uint32_t p0 = page;
     const uint32_t p1 = uint32_t(min(uint64_t(n_pages), uint64_t(page) + (item_end - item)));
+    const bool run_goes_on = item + (p1 - p0) < item_end;            // into the next request
 
     // Q^T operand: lane (n = head in group, jg) holds dims 32*kk + 8*jg .. +7
     uint4 qreg[KK];
@@ -276,12 +468,10 @@ void attn_mfma_kernel(AttnLaunch a) {
     // them with two pages of loads in flight ahead of the math.
     for (uint32_t base = p0; base < p1; base += 64) {
       const uint32_t cnt = min(64u, p1 - base);
-      const uint32_t it0 = uint32_t(item) + (base - p0);       // flattened index of page `base`
-      uint32_t my_slot;
-      if (it0 - item0 + cnt <= 64)                             // inside the preloaded window
-        my_slot = __shfl(my_win, int((lane + (it0 - item0)) & 63));
-      else
-        my_slot = lane < cnt ? a.slots[it0 + lane] : kDevUnmapped;
+      uint32_t my_slot = (pre_r == r && pre_base == base) ? pre_val : fetch_slots(r, base);
+      if (lane >= cnt) my_slot = kDevUnmapped;
+      if (base + 64 < p1) prefetch_slots(r, base + 64);
+      else if (run_goes_on) prefetch_slots(r + 1, 0);
       PageRegs<D> ra, rb, rc;
       const uint8_t* arena = a.P.arena;
       if (__ballot(lane < cnt && my_slot == kDevUnmapped) == 0) {
@@ -304,7 +494,7 @@ void attn_mfma_kernel(AttnLaunch a) {
           if (i + 2 < cnt) process(rc, min(16u, n_tok - (base + i + 2) * 16));
         }
       } else {
-        // some handle did not translate (counted by the translation kernel): skip those pages
+        // some handle did not translate (counted by the preparation kernel): skip those pages
         for (uint32_t i = 0; i < cnt; ++i) {
           const uint32_t slot = __builtin_amdgcn_readlane(my_slot, i);
           if (slot == kDevUnmapped) continue;
@@ -333,9 +523,7 @@ void attn_mfma_kernel(AttnLaunch a) {
         }
       }
     } else {
-      // a run leaves at most two partial results: slot 1 for the piece that starts its
-      // request, slot 0 for the piece that continues one
-      const size_t slot = (size_t(g) * a.runs + w) * 2 + (p0 == 0 ? 1 : 0);
+      const size_t slot = partial_slot(g, a.runs, w, p0 == 0);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const uint32_t head = 4 * jg + i;
@@ -357,87 +545,20 @@ void attn_mfma_kernel(AttnLaunch a) {
   }
 }
 
-// Combines the partial results of one (query head, request) in logical (run) order.
-// Workgroup of four wavefronts: up to 64 pieces (every request of an ordinary
-// batch) are handled by the first alone; a request spread over more runs (one long
-// request in a small batch) gives every wavefront each fourth group of 64 pieces
-// and the four partial sums are added in wavefront order.
-__global__ __launch_bounds__(256) void attn_merge_runs_kernel(AttnLaunch a) {
-  __shared__ float part_sum[3][256];        // wavefronts 1..3: partial output row (head_dim <= 256)
-  __shared__ float part_l[3];
-  const uint32_t j = blockIdx.x, r = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t D = a.head_dim, Hq = a.n_q_heads, Gq = Hq / a.n_kv_heads;
-  const uint32_t g = j / Gq, head = j % Gq;
-  float* orow = a.o + (size_t(r) * Hq + j) * D;
-  if (j == 0 && threadIdx.x == 0 &&
-      uint64_t(attended_tokens(a.ctx, r, a.append)) > uint64_t(a.max_pages) * 16u)
-    count_fault(a.P);
+// Merge of the partial results that the runs left: one wavefront per (KV head, request),
+// which handles the whole query group.  The runs that hold the request's first and last
+// page follow from its position on the plan's cost axis.
+template <int D>
+__global__ __launch_bounds__(64) void attn_merge_runs_kernel(AttnLaunch a) {
+  const uint32_t g = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
   const uint32_t start = a.prefix[r], end = a.prefix[r + 1];
-  if (start == end) {                       // no resident tokens: zero row
-    for (uint32_t d = threadIdx.x; d < D; d += 256) orow[d] = 0.f;
-    return;
-  }
-  // the runs that hold the request's first and last page (positions on the plan's cost axis)
+  if (start == end) return;                 // no resident tokens: the plan wrote the zero rows
   const uint64_t cpw = a.plan[1];
   const uint64_t at = uint64_t(start) + uint64_t(kRequestCost) * r + kRequestCost;
   const uint32_t wa = uint32_t(at / cpw), wb = uint32_t((at + (end - start) - 1) / cpw);
-  if (wa == wb) return;                     // one run covered it and wrote the row
-  const uint32_t np = wb - wa + 1;
-  const bool wide = np > 64;                // the same for the whole workgroup
-  if (!wide && wave != 0) return;
-  auto piece = [&](uint32_t k) -> size_t {  // first piece starts the request (slot 1)
-    return ((size_t(g) * a.runs + wa + k) * 2 + (k == 0 ? 1 : 0)) * Gq + head;
-  };
-  // the row maximum over all pieces
-  float M = -INFINITY;
-  for (uint32_t k = lane; k < np; k += 64) M = fmaxf(M, a.part_ml[piece(k) * 2]);
-  for (int o = 32; o; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-  // groups of 64 pieces: lane k holds piece k's weight, which is broadcast while the
-  // partial outputs are summed in piece order
-  float L = 0.f;
-  float sum[4] = {0.f, 0.f, 0.f, 0.f};      // output dims lane, lane + 64, ...
-  for (uint32_t base = wide ? 64 * wave : 0; base < np; base += wide ? 256 : 64) {
-    const uint32_t cnt = min(64u, np - base);
-    float wgt = 0.f;
-    if (lane < cnt) {
-      const size_t idx = piece(base + lane);
-      wgt = exp2f(a.part_ml[idx * 2] - M);
-      L += a.part_ml[idx * 2 + 1] * wgt;
-    }
-#pragma unroll
-    for (uint32_t q = 0; q < 4; ++q) {
-      const uint32_t d = 64 * q + lane;
-      if (64 * q >= D) break;
-      uint32_t k = 0;
-      for (; k + 4 <= cnt; k += 4) {
-        float v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = a.part_o[piece(base + k + u) * D + d];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) sum[q] += v[u] * __shfl(wgt, int(k + u));
-      }
-      for (; k < cnt; ++k) sum[q] += a.part_o[piece(base + k) * D + d] * __shfl(wgt, int(k));
-    }
-  }
-  for (int o = 32; o; o >>= 1) L += __shfl_xor(L, o);
-  if (wide) {
-    if (wave != 0) {
-#pragma unroll
-      for (uint32_t q = 0; q < 4; ++q) part_sum[wave - 1][64 * q + lane] = sum[q];
-      if (lane == 0) part_l[wave - 1] = L;
-    }
-    __syncthreads();
-    if (wave != 0) return;
-#pragma unroll
-    for (uint32_t w = 0; w < 3; ++w) {
-      L += part_l[w];
-#pragma unroll
-      for (uint32_t q = 0; q < 4; ++q) sum[q] += part_sum[w][64 * q + lane];
-    }
-  }
-#pragma unroll
-  for (uint32_t q = 0; q < 4; ++q)
-    if (64 * q < D) orow[64 * q + lane] = L > 0.f ? sum[q] / L : 0.f;
+  if (wa == wb) return;                     // one run covered it and wrote the rows
+  if (a.n_q_heads / a.n_kv_heads <= 4) merge_pieces<D, 4>(a, g, r, wa, wb - wa + 1, lane);
+  else merge_pieces<D, 16>(a, g, r, wa, wb - wa + 1, lane);
 }
 
 }  // namespace
@@ -455,19 +576,28 @@ uint32_t attention_runs_per_head(uint32_t n_kv_heads) {
   return runs ? runs : 1;
 }
 
-hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s) {
-  attn_plan_kernel<<<dim3(1), dim3(1024), 0, s>>>(a.ctx, a.batch, a.max_pages, a.runs, a.append,
-                                                  const_cast<uint32_t*>(a.plan),
-                                                  const_cast<uint32_t*>(a.prefix),
-                                                  const_cast<uint4*>(a.desc));
-  return hipGetLastError();
-}
-
-hipError_t launch_attention_translate(const AttnLaunch& a, const uint32_t* handles_all,
-                                      uint32_t n_attn, uint32_t* slots_all, hipStream_t s) {
-  const dim3 grid((a.max_pages + 255) / 256, a.batch, n_attn);
-  attn_translate_kernel<<<grid, dim3(256), 0, s>>>(a.P, handles_all, a.ctx, a.prefix, a.batch,
-                                                   a.max_pages, a.append, slots_all);
+hipError_t launch_attention_prepare(const AttnLaunch& a, const uint32_t* handles_all, uint32_t n_attn,
+                                    uint32_t* slots_all, float* o_all,
+                                    hipStream_t s) {
+  PrepareArgs p{};
+  p.P = a.P;
+  p.ctx = a.ctx;
+  p.handles = handles_all;
+  p.slots = slots_all;
+  p.plan = const_cast<uint32_t*>(a.plan);
+  p.prefix = const_cast<uint32_t*>(a.prefix);
+  p.desc = const_cast<uint4*>(a.desc);
+  p.o = o_all;
+  p.batch = a.batch;
+  p.max_pages = a.max_pages;
+  p.runs = a.runs;
+  p.append = a.append;
+  p.n_attn = n_attn;
+  p.row_floats = a.n_q_heads * a.head_dim;
+  const uint64_t entries = uint64_t(n_attn) * a.batch * a.max_pages;
+  const uint64_t blocks = 1 + (entries + 4095) / 4096;
+  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  attn_prepare_kernel<<<dim3(uint32_t(blocks)), dim3(1024), 0, s>>>(p);
   return hipGetLastError();
 }
 
@@ -482,7 +612,12 @@ hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s) {
 }
 
 hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s) {
-  attn_merge_runs_kernel<<<dim3(a.n_q_heads, a.batch), dim3(256), 0, s>>>(a);
+  const dim3 grid(a.n_kv_heads, a.batch);
+  switch (a.head_dim) {
+    case 64: attn_merge_runs_kernel<64><<<grid, dim3(64), 0, s>>>(a); break;
+    case 128: attn_merge_runs_kernel<128><<<grid, dim3(64), 0, s>>>(a); break;
+    default: attn_merge_runs_kernel<256><<<grid, dim3(64), 0, s>>>(a); break;
+  }
   return hipGetLastError();
 }
 

@@ -341,6 +341,9 @@ int check_step(avmp_pools* p, const avmp_step_t* st, uint32_t* n_attn_out, uint3
   if (n_attn && st->batch &&
       (!st->kv_handles || !st->ctx || !st->q || !st->o || st->max_pages == 0))
     return fail(AVMP_ERR_INVALID_ARG, "attention layers need kv_handles, ctx, q, o, max_pages");
+  if (n_attn && st->batch &&
+      ((reinterpret_cast<uintptr_t>(st->q) | reinterpret_cast<uintptr_t>(st->o)) & 15u))
+    return fail(AVMP_ERR_INVALID_ARG, "q and o must be 16-byte aligned");
   if ((st->k_new == nullptr) != (st->v_new == nullptr))
     return fail(AVMP_ERR_INVALID_ARG, "k_new and v_new go together");
   const bool conv = p->cfg.ssm_conv_kernel != 0;
@@ -411,9 +414,8 @@ int run_step(avmp_pools* p, const avmp_step_t* st, hipStream_t s, uint32_t n_att
         HIP_TRY(avmp::launch_kv_append(a, s));
       }
       if (mfma && !planned) {            // context lengths are the same for every layer
-        ProfScope scope(p, profile, AVMP_K_TABLE, s);
-        HIP_TRY(avmp::launch_attention_plan(a, s));
-        HIP_TRY(avmp::launch_attention_translate(a, st->kv_handles, n_attn, slots_base, s));
+        ProfScope scope(p, profile, AVMP_K_ATTENTION_PREPARE, s);
+        HIP_TRY(avmp::launch_attention_prepare(a, st->kv_handles, n_attn, slots_base, st->o, s));
         planned = true;
       }
       {

@@ -29,7 +29,7 @@ struct AttnLaunch {
   const uint32_t* prefix;    // device [batch + 1]: page prefix sums
   const uint4* desc;         // device [runs]: each run's first (request, page) and its stretch
                              // [first, last) of the batch's page sequence
-  const uint32_t* slots;     // device [total pages]: this layer's pre-translated slots, run order
+  const uint32_t* slots;     // device [batch][max_pages]: this layer's pre-translated slots
   uint32_t runs;             // runs (wavefronts) per KV head
 };
 
@@ -70,10 +70,10 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 bool attention_mfma_supported(uint32_t dtype, uint32_t n_q_heads, uint32_t n_kv_heads,
                               uint32_t head_dim);
 uint32_t attention_runs_per_head(uint32_t n_kv_heads);
-hipError_t launch_attention_plan(const AttnLaunch& a, hipStream_t s);   // once per decode step
-// once per decode step, after the plan: handles of all attention layers -> slots
-hipError_t launch_attention_translate(const AttnLaunch& a, const uint32_t* handles_all,
-                                      uint32_t n_attn, uint32_t* slots_all, hipStream_t s);
+// once per decode step: run plan, zero rows of empty requests (o_all is
+// [n_attn][batch][Hq][D]) and the handles of all attention layers -> slots
+hipError_t launch_attention_prepare(const AttnLaunch& a, const uint32_t* handles_all, uint32_t n_attn,
+                                    uint32_t* slots_all, float* o_all, hipStream_t s);
 hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s);
