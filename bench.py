@@ -26,44 +26,91 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 PREWARM_STEPS = 10
 
-# HBM bytes per launch of the SSM kernel at this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# runs scaled by the same counters' readings for the plain migration copy (summary under
-# profiles/).  Valid only for the kernel source it was measured on: reported as null otherwise.
-SSM_TRAFFIC = {"source_sha256_16": "8e85746839f00ea0", "batch": 64, "bytes_per_launch": 527271 * 1024}
+# Counter-measured HBM traffic per launch, written by `bench.py --write-traffic` from two
+# `rocprofv3 --pmc` runs of the default bench (FETCH_SIZE, then WRITE_SIZE) and read back here.
+# A figure is reported only for the workload it was measured on and only while the kernel
+# source still has the digest it was measured with; otherwise `traffic` is null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SOURCES = {
+    # the fp32-state kernel and the access helpers it streams its tile with: from the helpers'
+    # comment to the start of the bf16-state section
+    "ssm": ("ssm_update.hip", "// The state tile goes through buffer accesses",
+            "// Same update with the state stored as bf16"),
+    "attention": ("attn_mfma.hip", None, None),          # attention + merge + preparation kernels
+}
+KERNEL_MATCH = {"ssm": ("ssm_update_kernel",), "attention": ("attn_mfma_kernel", "attn_merge_runs_kernel")}
 
 
-# The same for the attention kernel (whole source file hashed).
-ATTN_TRAFFIC = {"source_sha256_16": "408a3bb3b3798060", "batch": 64, "bytes_per_launch": 272775 * 1024}
-
-
-def attn_traffic(batch, workload, seed):
+def source_digest(kind):
     import hashlib
-    src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "attn_mfma.hip")
+    name, start, stop = KERNEL_SOURCES[kind]
     try:
-        digest = hashlib.sha256(open(src).read().encode()).hexdigest()[:16]
-    except OSError:
-        return None
-    if (digest != ATTN_TRAFFIC["source_sha256_16"] or batch != ATTN_TRAFFIC["batch"]
-            or workload != "uniform_short" or seed != WORKLOADS["uniform_short"]["seed"]):
-        return None
-    return ATTN_TRAFFIC["bytes_per_launch"]
-
-
-def ssm_traffic(batch):
-    import hashlib
-    src = os.path.join(ROOT, "paper_2605_22416_amd", "csrc", "ssm_update.hip")
-    try:
-        text = open(src).read()
-        # the fp32-state kernel and the access helpers it streams its tile with: from the
-        # helpers' comment to the start of the bf16-state section
-        i = text.index("// The state tile goes through buffer accesses")
-        j = text.index("// Same update with the state stored as bf16")
-        digest = hashlib.sha256(text[i:j].encode()).hexdigest()[:16]
+        text = open(os.path.join(ROOT, "paper_2605_22416_amd", "csrc", name)).read()
+        if start is not None:
+            text = text[text.index(start):text.index(stop)]
     except (OSError, ValueError):
         return None
-    if digest != SSM_TRAFFIC["source_sha256_16"] or batch != SSM_TRAFFIC["batch"]:
+    return hashlib.sha256(text.encode()).hexdigest()[:16]
+
+
+def measured_traffic(kind, batch, workload, seed):
+    """HBM bytes per layer of one kernel kind from profiles/traffic.json, or None."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
         return None
-    return SSM_TRAFFIC["bytes_per_launch"]
+    k = rec.get("kernels", {}).get(kind)
+    if (k is None or k.get("source_sha256_16") != source_digest(kind) or rec.get("batch") != batch
+            or rec.get("workload") != workload or rec.get("seed") != seed):
+        return None
+    return k["bytes_per_layer"]
+
+
+def write_traffic(fetch_csv, write_csv, batch, workload, seed):
+    """Turns the counter_collection.csv files of two rocprofv3 --pmc runs of this bench
+    (FETCH_SIZE and WRITE_SIZE, KiB per dispatch) into profiles/traffic.json.  Each counter is
+    scaled by what it reads for the migration copy kernel, whose dispatches move a known number
+    of bytes each way: grid size / 1024 work-items per 64 KiB page."""
+    import csv
+    page = 65536
+    out = {"batch": batch, "workload": workload, "seed": seed, "kernels": {}, "scale": {},
+           "unit": "HBM bytes per layer (fetch + write), averaged over the run's launches"}
+    per_kind = {}
+    for counter, path in (("FETCH_SIZE", fetch_csv), ("WRITE_SIZE", write_csv)):
+        known = seen = 0.0
+        sums = {k: [0.0, 0] for k in KERNEL_MATCH}
+        parts = {k: {m: [0.0, 0] for m in KERNEL_MATCH[k]} for k in KERNEL_MATCH}
+        for row in csv.DictReader(open(path)):
+            if row["Counter_Name"] != counter:
+                continue
+            name, val = row["Kernel_Name"], float(row["Counter_Value"]) * 1024.0
+            if "migrate_copy_kernel" in name:
+                known += int(row["Grid_Size"]) // 1024 * page
+                seen += val
+            for kind, matches in KERNEL_MATCH.items():
+                for m in matches:
+                    if m in name:
+                        parts[kind][m][0] += val
+                        parts[kind][m][1] += 1
+        if seen <= 0:
+            raise SystemExit("no migrate_copy_kernel dispatch in %s: cannot scale %s" % (path, counter))
+        scale = known / seen
+        out["scale"][counter] = {"factor": scale, "copy_bytes_known": known, "copy_bytes_read": seen}
+        for kind in KERNEL_MATCH:
+            total = sum(v[0] / v[1] for v in parts[kind].values() if v[1])     # per launch, kernels of a layer added
+            per_kind.setdefault(kind, {})[counter] = total * scale
+    for kind, c in per_kind.items():
+        out["kernels"][kind] = {"bytes_per_layer": int(round(c["FETCH_SIZE"] + c["WRITE_SIZE"])),
+                                "fetch_bytes": int(round(c["FETCH_SIZE"])), "write_bytes": int(round(c["WRITE_SIZE"])),
+                                "kernels": list(KERNEL_MATCH[kind]), "source_sha256_16": source_digest(kind)}
+    out["command"] = ("rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o f -- python3 bench.py "
+                      "--no-cpu-baseline --no-kernel-events --steps 4 --warmup 1   (and the same with "
+                      "WRITE_SIZE); then python3 bench.py --write-traffic <f_counter_collection.csv> "
+                      "<w_counter_collection.csv>")
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    print(json.dumps(out))
 
 
 def attention_bytes(spec, ctx):
@@ -205,6 +252,10 @@ def main():
     ap.add_argument("--vmm-chunk-kib", type=int, default=None,
                     help="chunk size of the vmm arena (default 1 GiB; 2 MiB for --migration-compare, "
                          "where units must be whole chunks)")
+    ap.add_argument("--write-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="instead of the benchmark: write profiles/traffic.json from the "
+                         "counter_collection.csv files of two rocprofv3 --pmc runs of this bench "
+                         "(FETCH_SIZE, WRITE_SIZE)")
     ap.add_argument("--migration-compare", action="store_true",
                     help="instead of the decode benchmark: time migrations of the same pools done "
                          "by copy and by exchanging physical chunks, on a vmm arena")
@@ -213,6 +264,13 @@ def main():
         print("bench.py: this path runs on ONE GPU (pools, table and kernels are device-local; "
               "no collectives exist to measure); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.write_traffic:
+        wl = WORKLOADS[args.workload]
+        write_traffic(args.write_traffic[0], args.write_traffic[1],
+                      wl["batch"] if args.batch is None else args.batch, args.workload,
+                      wl["seed"] if args.seed is None else args.seed)
+        return
 
     import numpy as np
     import torch
@@ -405,7 +463,7 @@ def main():
         a = kernels["ssm"]["GBps"]
         roofline = {"kernel": "ssm_update_kernel", "bound": "hbm", "achieved": a,
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                    "traffic": ssm_traffic(sc.batch)
+                    "traffic": measured_traffic("ssm", sc.batch, args.workload, args.seed)
                     if args.state_dtype == "f32" and not spec.conv_kernel else None,
                     "bytes_per_launch": per_launch["ssm"],
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
@@ -426,7 +484,7 @@ def main():
         roofline_attention = {"kernel": "attn_mfma_kernel + attn_prepare_kernel / attention layers",
                               "bound": "hbm", "achieved": a,
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
-                              "traffic": attn_traffic(sc.batch, args.workload, args.seed),
+                              "traffic": measured_traffic("attention", sc.batch, args.workload, args.seed),
                               "bytes_per_launch": attn_layer_bytes,
                               "avg_layer_us": layer_us, "avg_us_by_kernel": parts}
 
