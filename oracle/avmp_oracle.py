@@ -333,6 +333,31 @@ class Pools:
         self.bytes_wasted += res.bytes_wasted
         return res
 
+    def absorb_gap(self, pool: int) -> MigrateResult:
+        """Give `pool` the whole units that fit into the gap between the pools.
+
+        The gap holds what earlier migrations left over ("donor bytes freed modulo
+        the recipient page size") and whatever the arena had beyond the initial
+        capacities; nobody owns those bytes, so no donor shrinks and nothing is
+        copied.  The new slots are the ones just above the pool's capacity; the
+        remainder stays in the gap and is counted as this step's wasted bytes.
+        A gap smaller than one unit changes nothing (ERR_CAPACITY).
+        """
+        if pool not in (POOL_KV, POOL_SSM):
+            return MigrateResult(ERR_INVALID_ARG)
+        self.ops += 1
+        gain = self.gap // self.unit[pool]
+        if gain == 0:
+            return MigrateResult(ERR_CAPACITY)
+        self.capacity[pool] += gain
+        self.gap -= gain * self.unit[pool]
+        res = MigrateResult(OK)
+        res.recipient_gain = gain
+        res.bytes_wasted = self.gap
+        self.migrations += 1
+        self.bytes_wasted += res.bytes_wasted
+        return res
+
     def stats(self) -> dict:
         return {
             "capacity": tuple(self.capacity),
@@ -597,6 +622,20 @@ class Pools:
 # the donor's free units); one failing allocate() may take several transitions
 # in a row (BALANCED -> X_PRESSURED -> REBALANCING -> BALANCED); after a
 # migration the allocation is retried once.
+#
+# Text against figure.  The Method text starts a migration on a CapacityError
+# with a donor above threshold_high; Fig. 2 reaches REBALANCING only through
+# X_PRESSURED, i.e. only when the failing pool's own free fraction is below
+# threshold_low.  The figure is followed: a multi-unit request that fails while
+# its pool still has threshold_low or more free does not rebalance, and a
+# failure in pool Y while the machine sits in X_PRESSURED is ignored until X
+# recovers.
+#
+# Bytes that nobody owns.  When the gap between the pools already holds the B
+# units the step would give (left-overs of earlier migrations, or an arena
+# larger than the initial capacities), the step takes them from the gap: no
+# donor is needed, so the threshold_high test does not apply, but it is a
+# rebalance like any other (throttled, counted, REBALANCING -> BALANCED).
 # ----------------------------------------------------------------------------
 BALANCED = 0
 KV_PRESSURED = 1
@@ -634,12 +673,12 @@ class Rebalancer:
         code, hs = self.pools.alloc(pool, n)
         if code != ERR_CAPACITY:
             return code, hs, 0
-        moved = self._capacity_error_handler(pool)
+        moved = self._capacity_error_handler(pool)     # donor units, 0: no rebalance, -1: from the gap
         if moved:
             code, hs = self.pools.alloc(pool, n)
         if code == ERR_CAPACITY:
             self.oom_events += 1
-        return code, hs, moved
+        return code, hs, max(moved, 0)
 
     def _capacity_error_handler(self, pool: int) -> int:
         pol, p = self.policy, self.pools
@@ -654,20 +693,22 @@ class Rebalancer:
             self.state = pressured
         if self.state != pressured:
             return 0
-        if not (self.free_fraction(other) > pol.threshold_high):
+        need_bytes = pol.migration_batch_size * p.unit[pool] - p.gap
+        from_gap = need_bytes <= 0                     # the gap alone holds the step's B units
+        if not from_gap and not (self.free_fraction(other) > pol.threshold_high):
             return 0                                   # no donor: static-partition behaviour
         if self.last_rebalance_op is not None and \
                 p.ops - self.last_rebalance_op < pol.min_rebalance_interval_ops:
             return 0                                   # throttled
-        need_bytes = pol.migration_batch_size * p.unit[pool] - p.gap
-        donor_units = max(0, -(-need_bytes // p.unit[other]))
-        donor_units = min(donor_units, p.free_count(other))
-        if donor_units == 0:
-            return 0
+        donor_units = 0
+        if not from_gap:
+            donor_units = min(-(-need_bytes // p.unit[other]), p.free_count(other))
+            if donor_units == 0:
+                return 0
         self.state = REBALANCING
-        res = p.migrate(other, donor_units)
+        res = p.absorb_gap(pool) if from_gap else p.migrate(other, donor_units)
         assert res.code == OK
         self.rebalance_count += 1
         self.last_rebalance_op = p.ops
         self.state = BALANCED                          # migration complete
-        return donor_units
+        return -1 if from_gap else donor_units

@@ -49,8 +49,15 @@ MUTATIONS = [
     ("bf16 rounds toward zero", "q = np.ldexp(np.rint(np.ldexp(v, -qe)), qe)", "q = np.ldexp(np.trunc(np.ldexp(v, -qe)), qe)"),
     ("append lands one slot late", "self.write_kv_token(int(handles[r, t // T]), t % T, k_new[r], v_new[r])", "self.write_kv_token(int(handles[r, (t + 1) // T]), (t + 1) % T, k_new[r], v_new[r])"),
     ("append without attending the new token", "o.append(self.paged_attention(kv_handles[ia], ctx + 1, q[ia]))", "o.append(self.paged_attention(kv_handles[ia], ctx, q[ia]))"),
-    ("donor needs only threshold_low", "if not (self.free_fraction(other) > pol.threshold_high):", "if not (self.free_fraction(other) > pol.threshold_low):"),
-    ("donor test not strict", "if not (self.free_fraction(other) > pol.threshold_high):", "if not (self.free_fraction(other) >= pol.threshold_high):"),
+    ("donor needs only threshold_low", "not (self.free_fraction(other) > pol.threshold_high):", "not (self.free_fraction(other) > pol.threshold_low):"),
+    ("donor test not strict", "not (self.free_fraction(other) > pol.threshold_high):", "not (self.free_fraction(other) >= pol.threshold_high):"),
+    ("gap step still asks for a donor", "if not from_gap and not (self.free_fraction(other)", "if not (self.free_fraction(other)"),
+    ("gap step taken when the gap is short of B units", "from_gap = need_bytes <= 0", "from_gap = need_bytes <= p.unit[pool]"),
+    ("gap step never taken", "from_gap = need_bytes <= 0", "from_gap = False"),
+    ("gap step escapes the throttle", "        if self.last_rebalance_op is not None and \\\n", "        if not from_gap and self.last_rebalance_op is not None and \\\n"),
+    ("absorbed units counted in the other pool's size", "        gain = self.gap // self.unit[pool]\n", "        gain = self.gap // self.unit[1 - pool]\n"),
+    ("absorbing empties the gap", "        self.gap -= gain * self.unit[pool]", "        self.gap = 0"),
+    ("absorbing a short gap is not refused", "        if gain == 0:\n            return MigrateResult(ERR_CAPACITY)", "        if gain < 0:\n            return MigrateResult(ERR_CAPACITY)"),
     ("throttle ignored", "                p.ops - self.last_rebalance_op < pol.min_rebalance_interval_ops:\n            return 0", "                False:\n            return 0"),
     ("throttle off by one", "p.ops - self.last_rebalance_op < pol.min_rebalance_interval_ops", "p.ops - self.last_rebalance_op <= pol.min_rebalance_interval_ops"),
     ("pressure test inverted", "if self.state == BALANCED and self.free_fraction(pool) < pol.threshold_low:", "if self.state == BALANCED and self.free_fraction(pool) > pol.threshold_low:"),

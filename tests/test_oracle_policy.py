@@ -152,3 +152,54 @@ def test_migrations_happen_only_inside_failing_allocations():
         st = p.stats()
         assert st["capacity"][0] * UK + st["capacity"][1] * US + st["gap_bytes"] == p.usable
     assert rb.rebalance_count == p.migrations > 3
+
+
+def test_a_gap_that_holds_the_step_is_used_without_a_donor():
+    """Bytes between the pools belong to nobody: when they already hold the B units a
+    step gives, the step takes them from there, with no donor and no copy, but as a
+    rebalance like any other (counted, throttled)."""
+    pol = orc.Policy(migration_batch_size=4, min_rebalance_interval_ops=30)
+    # arena with room for 5 pages and half a page more than the pools take
+    p = orc.Pools(TINY, 10 * UK + 10 * US + 5 * UK + US, 10, 10, with_data=False)
+    rb = orc.Rebalancer(p, pol)
+    rb.allocate(0, 10)
+    rb.allocate(1, 9)                        # SSM 1 of 10 free: never a donor
+    code, hs, moved = rb.allocate(0, 2)      # KV fails; the gap holds 5 >= 4 pages
+    assert (code, len(hs), moved) == (orc.OK, 2, 0)
+    st = p.stats()
+    assert st["capacity"] == (15, 10) and st["gap_bytes"] == US      # every whole page of the gap, remainder kept
+    assert (p.migrations, p.units_copied, p.bytes_migrated, rb.rebalance_count) == (1, 0, 0, 1)
+    assert rb.state == orc.BALANCED and rb.oom_events == 0
+    # the next step is throttled like after any rebalance, and then finds no whole step in the gap
+    rb.allocate(0, 3)
+    assert rb.allocate(0, 1)[0] == orc.ERR_CAPACITY and rb.rebalance_count == 1
+    while p.ops - rb.last_rebalance_op < 30 - 1:
+        assert rb.allocate(0, 1) == (orc.ERR_CAPACITY, [], 0)
+    assert rb.allocate(0, 1) == (orc.ERR_CAPACITY, [], 0)            # gap 8 KiB < 4 pages, SSM no donor: static
+    assert p.stats()["capacity"] == (15, 10) and rb.rebalance_count == 1
+
+
+def test_a_step_from_the_gap_is_throttled_like_any_other():
+    pol = orc.Policy(migration_batch_size=1, min_rebalance_interval_ops=40)
+    p = orc.Pools(TINY, 4 * UK + 4 * US + US, 4, 4, with_data=False)         # gap: one block
+    rb = orc.Rebalancer(p, pol)
+    rb.allocate(0, 4)                        # KV full: never a donor
+    rb.allocate(1, 4)
+    assert rb.allocate(1, 1)[0] == orc.OK and rb.rebalance_count == 1 and p.stats()["capacity"] == (4, 5)
+    # put a block's worth back into the gap by hand, inside the throttle window
+    p.free([orc.encode_handle(1, 4)])
+    assert p.migrate(1, 1).recipient_gain == 0 and p.gap == US
+    assert rb.allocate(1, 1) == (orc.ERR_CAPACITY, [], 0) and rb.rebalance_count == 1
+    while p.ops - rb.last_rebalance_op < 40 - 1:
+        assert rb.allocate(1, 1)[0] == orc.ERR_CAPACITY
+    assert rb.allocate(1, 1)[0] == orc.OK and rb.rebalance_count == 2 and p.gap == 0
+
+
+def test_a_gap_short_of_the_step_still_counts_towards_it():
+    """With less than B units in the gap the donor gives the difference, as before."""
+    pol = orc.Policy(migration_batch_size=4, min_rebalance_interval_ops=0)
+    p = orc.Pools(TINY, 10 * UK + 40 * US + 3 * UK, 10, 40, with_data=False)    # gap: 3 pages
+    rb = orc.Rebalancer(p, pol)
+    rb.allocate(0, 10)
+    code, hs, moved = rb.allocate(0, 1)      # 4 pages wanted, 3 in the gap: 2 blocks = 1 page from SSM
+    assert (code, moved) == (orc.OK, 2) and p.stats()["capacity"] == (14, 38) and p.gap == 0

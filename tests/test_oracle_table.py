@@ -349,3 +349,36 @@ def test_same_trace_twice_is_identical():
         log.append(tuple(sorted(p.stats().items())))
         logs.append(log)
     assert logs[0] == logs[1]
+
+
+def test_absorb_gap_closed_forms_and_round_trip():
+    """The gap's whole units go to the pool that asks; the remainder stays; nothing else moves."""
+    uk, us = TINY.unit_bytes(0), TINY.unit_bytes(1)          # 16 KiB, 8 KiB
+    extra = 3 * uk + us // 2
+    p = orc.Pools(TINY, 6 * uk + 4 * us + extra, 6, 4, with_data=False)
+    assert p.gap == extra - extra % 128 or p.gap == extra     # usable is the arena rounded down to 128
+    g0 = p.gap
+    _, live = p.alloc(0, 6)
+    before = p.stats()
+    assert p.absorb_gap(2).code == orc.ERR_INVALID_ARG and p.stats() == before     # bad pool: not even counted
+    r = p.absorb_gap(0)
+    assert (r.code, r.units_copied, r.recipient_gain, r.bytes_wasted) == (orc.OK, 0, g0 // uk, g0 % uk)
+    st = p.stats()
+    assert st["capacity"] == (6 + g0 // uk, 4) and st["gap_bytes"] == g0 % uk
+    assert st["capacity"][0] * uk + st["capacity"][1] * us + st["gap_bytes"] == p.usable
+    assert (st["migrations"], st["units_copied"], st["bytes_migrated"], st["bytes_wasted"]) == (1, 0, 0, g0 % uk)
+    assert st["ops"] == before["ops"] + 1
+    # exactly the gained pages can be allocated now, in the slots just above the old capacity
+    code, hs = p.alloc(0, g0 // uk)
+    assert code == orc.OK and sorted(p.resolve(h)[1] for h in hs) == list(range(6, 6 + g0 // uk))
+    assert p.alloc(0, 1)[0] == orc.ERR_CAPACITY
+    assert [p.resolve(h)[1] for h in live] == list(range(6))                        # nobody moved
+    # a gap smaller than one unit: refused, nothing changes but the operation counter
+    before = p.stats()
+    r = p.absorb_gap(0)
+    after = p.stats()
+    assert r.code == orc.ERR_CAPACITY and {**after, "ops": before["ops"]} == before
+    # what a migration leaves over can be taken back: one block to the page pool leaves 8 KiB in the gap
+    q = orc.Pools(TINY, 4 * uk + 4 * us, 4, 4, with_data=False)
+    assert q.migrate(1, 1).recipient_gain == 0 and q.gap == us and q.stats()["capacity"] == (4, 3)
+    assert q.absorb_gap(1).recipient_gain == 1 and q.gap == 0 and q.stats()["capacity"] == (4, 4)
