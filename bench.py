@@ -135,25 +135,113 @@ def ssm_bytes(spec):
     return 2 * H * P * N * spec.state_bytes + H * P * e + H * P * 4 + 2 * N * e + H * 4 + 8
 
 
-def cpu_baseline(spec, sc, inp, seed, budget_s=12.0, max_requests=64, conv=None):
-    """Times the CPU oracle, as it stands, on the first requests of the batch
-    (all 32 layers each) until about budget_s seconds of work are done."""
+# ---- the CPU oracle, timed on the host cores (runs before anything touches the GPU, so that
+# ---- worker processes can be forked) ---------------------------------------------------------
+_ORACLE_JOB = {}
+
+
+def _oracle_request(r):
+    """One request through all layers of the oracle; worker-side.  Returns float32 outputs."""
+    import numpy as np
     from oracle.sampled import RequestReference
-    done, elapsed, nbytes = [], 0.0, 0
-    ref_o, ref_y = {}, {}
-    for r in range(min(max_requests, sc.batch)):
+    j = _ORACLE_JOB
+    ref = RequestReference(j["spec"], j["seed"], r, int(j["ctx"][r]), bool(j["fresh"][r]))
+    t0 = time.perf_counter()
+    o, y = ref.step(j["inp"], j["conv"])
+    return r, time.perf_counter() - t0, o.astype(np.float32), y.astype(np.float32)
+
+
+def _worker_init():
+    try:                                  # one numeric thread per worker process
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)
+    except Exception:
+        pass
+
+
+def host_workers():
+    """Worker processes for the all-cores leg: the cores this process may run on, at most 16
+    (a GPU machine's share per GPU)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def oracle_pool_run(spec, seed, ctx, fresh, inp, conv, workers, keep_outputs):
+    """Every request of a batch through the oracle, one request per task, longest first, on
+    `workers` forked processes.  Returns (wall seconds, summed worker seconds, outputs)."""
+    import multiprocessing as mp
+    import numpy as np
+    _ORACLE_JOB.update(spec=spec, seed=seed, ctx=ctx, fresh=fresh, inp=inp, conv=conv)
+    order = [int(r) for r in np.argsort(-np.asarray(ctx, dtype=np.int64), kind="stable")]
+    outs, busy = {}, 0.0
+    with mp.get_context("fork").Pool(workers, initializer=_worker_init) as pool:
+        pool.map(abs, range(workers))     # processes are up before the clock starts
+        t0 = time.perf_counter()
+        for r, dt, o, y in pool.imap_unordered(_oracle_request, order, chunksize=1):
+            busy += dt
+            if keep_outputs:
+                outs[r] = (o, y)
+        wall = time.perf_counter() - t0
+    _ORACLE_JOB.clear()
+    return wall, busy, outs
+
+
+def batch_bytes(spec, ctx):
+    return sum(spec.n_attn * attention_bytes(spec, c) + spec.n_ssm * ssm_bytes(spec) for c in ctx)
+
+
+def cpu_baseline(spec, sc, inp, seed, conv=None, single_budget_s=6.0, others=True):
+    """The oracle as it stands, on the host: every request of the batch once over all host
+    cores (forked workers, a request per task), a single-thread leg on the first requests,
+    and the other workload shapes (mixed_long at full size; agentic_burst and capacity cut to
+    an eighth, as stated in their entries).  Returns (record, {request: (o, y)})."""
+    from gen import inputs
+    from oracle.sampled import RequestReference
+    workers = host_workers()
+    wall, busy, outs = oracle_pool_run(spec, seed, sc.ctx, sc.fresh, inp, conv, workers, True)
+    nbytes = batch_bytes(spec, sc.ctx)
+    rec = {"value": nbytes / wall / 1e9, "unit": "GB/s", "cores": workers,
+           "cores_available": os.cpu_count(), "kind": "oracle",
+           "sample": "all %d requests of the batch (all %d layers each), one request per task on %d "
+                     "forked worker processes: %.1f s of wall time, %.1f s of worker time, same "
+                     "algorithmic-byte numerator" % (sc.batch, len(spec.layer_kinds), workers, wall, busy),
+           "us_per_step": wall * 1e6}
+    # single thread, in this process
+    done, elapsed = 0, 0.0
+    for r in range(sc.batch):
         ref = RequestReference(spec, seed, r, int(sc.ctx[r]), bool(sc.fresh[r]))
         t0 = time.perf_counter()
-        ref_o[r], ref_y[r] = ref.step(inp, conv)
+        ref.step(inp, conv)
         elapsed += time.perf_counter() - t0
-        nbytes += spec.n_attn * attention_bytes(spec, sc.ctx[r]) + spec.n_ssm * ssm_bytes(spec)
-        done.append(r)
-        if elapsed >= budget_s and len(done) >= 2:
+        done += 1
+        if elapsed >= single_budget_s and done >= 2:
             break
-    return {"value": nbytes / elapsed / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "requests 0..%d of the batch (all %d layers each), %.1f s of oracle time, "
-                      "same algorithmic-byte numerator" % (done[-1], len(spec.layer_kinds), elapsed),
-            "us_per_step_extrapolated": elapsed / len(done) * sc.batch * 1e6}, ref_o, ref_y
+    rec["single_thread"] = {"value": batch_bytes(spec, sc.ctx[:done]) / elapsed / 1e9, "unit": "GB/s",
+                            "cores": 1, "sample": "requests 0..%d, %.1f s" % (done - 1, elapsed),
+                            "us_per_step_extrapolated": elapsed / done * sc.batch * 1e6}
+    if others and not spec.conv_kernel and spec.state_dtype == "f32":
+        import numpy as np
+        rec["other_configs"] = {}
+        plans = [("mixed_long", 32, 1003, None, "full size: batch 32"),
+                 ("agentic_burst", 32, 1004, None, "an eighth: batch 32 of 256"),
+                 ("capacity", 64, 1005, 32768,
+                  "an eighth: 64 of the 512 requests U[1024,8192] and one long request of 32768 tokens "
+                  "(the workload has four of 262144)")]
+        for name, batch, wseed, long_ctx, what in plans:
+            wsc = inputs.make_scenario(spec, name, batch, wseed)
+            ctx, fresh = wsc.ctx, wsc.fresh
+            if long_ctx is not None:
+                ctx = np.concatenate([ctx[:batch], np.array([long_ctx], dtype=np.uint32)])
+                fresh = np.zeros(len(ctx), dtype=bool)
+            winp = inputs.step_inputs(spec, len(ctx), wseed)
+            w, bsy, _ = oracle_pool_run(spec, wseed, ctx, fresh, winp, None, workers, False)
+            rec["other_configs"][name] = {"value": batch_bytes(spec, ctx) / w / 1e9, "unit": "GB/s",
+                                          "cores": workers, "sample": what, "us_per_step": w * 1e6,
+                                          "worker_seconds": bsy, "tokens": int(np.asarray(ctx, dtype=np.int64).sum())}
+    return rec, outs
 
 
 # The default workload is the one the headline metric is quoted on; the others are the
@@ -174,6 +262,77 @@ WORKLOADS = {
                      churn=(272, 28), mig_pages=128, sweep=(64, 1024, 16384),
                      text="capacity: U[1024,8192] + 4 x 262144 tokens, pools filling about 200 GB"),
 }
+
+
+def capacity_migration_sweep(spec, stream, batches=((64, 6), (1024, 6), (16384, 4))):
+    """Migration batches of 64, 1024 and 16384 pages on pools that fill about 200 GB of HBM
+    (the capacity-scale workload's pools: 512 requests of U[1024,8192] tokens plus four of
+    262144), worst case: the KV pool's slots are ranked from the top down, so the live pages
+    occupy its highest slots and EVERY slot a migration vacates holds a live page that has to
+    be copied.  Contents are whatever the fresh arena holds (a copy does not care).  Capacity
+    is not given back between batches: each one vacates the next stretch of live pages.
+    Wall time of the avmp_migrate call up to the end of its copies, device idle before."""
+    import numpy as np
+    import torch
+    from gen import inputs
+    from paper_2605_22416_amd import binding as av
+    sc = inputs.make_scenario(spec, "capacity", 512, 1005, headroom=1.7, permute=False)
+    need = sc.arena_bytes + (2 << 30)
+    free = torch.cuda.mem_get_info()[0]
+    if free < need:
+        return {"skipped": "needs %.0f GB of free HBM, %.0f GB are free" % (need / 1e9, free / 1e9)}
+    n_slots = sc.arena_bytes // spec.kv_page_bytes
+    top_down = np.arange(n_slots - 1, -1, -1, dtype=np.uint32)       # rank of slot s: highest slot first
+    arena = torch.empty(sc.arena_bytes, dtype=torch.uint8, device="cuda:0")
+    cfg, keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.ssm_heads,
+                               spec.ssm_headdim, spec.ssm_dstate, sc.kv_capacity, sc.ssm_capacity,
+                               slot_rank=[top_down, None])
+    rc, p = av.avmp_pools_create(cfg, arena, sc.arena_bytes)
+    assert rc == av.AVMP_OK, av.avmp_last_error()
+    live = int(sc.n_pages.sum()) * spec.n_attn
+    left = live
+    while left:
+        n = min(left, 1 << 18)
+        rc, _ = av.avmp_alloc(p, 0, n)
+        assert rc == av.AVMP_OK, av.avmp_last_error()
+        left -= n
+    assert av.avmp_flush(p, stream) == av.AVMP_OK
+    torch.cuda.synchronize()
+    rows = []
+    av.avmp_profile_enable(p, True)
+    for n, reps in batches:
+        walls, kernels = [], []
+        for _ in range(reps):
+            av.avmp_profile_read(p, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rc, res = av.avmp_migrate(p, 0, n, stream)
+            t1 = time.perf_counter()
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            assert rc == av.AVMP_OK and res.units_copied == n, (rc, res.units_copied, av.avmp_last_error())
+            rc, pr = av.avmp_profile_read(p, stream)
+            walls.append((t2 - t0, t1 - t0))
+            kernels.append(pr["migrate_copy"][0] * 1e-3)
+        wall = sorted(w for w, _ in walls)[len(walls) // 2]
+        host = sorted(h for _, h in walls)[len(walls) // 2]
+        kern = sorted(kernels)[len(kernels) // 2]
+        moved = 2.0 * n * spec.kv_page_bytes
+        rows.append({"pages": n, "pages_copied": n, "repeats": reps, "us_wall_median": wall * 1e6,
+                     "us_host_call_median": host * 1e6, "us_copy_kernels_median": kern * 1e6,
+                     "pages_per_s_wall": n / wall, "GBps_wall": moved / wall / 1e9,
+                     "GBps_copy_kernels": moved / kern / 1e9 if kern > 0 else None,
+                     "pages_per_s_best": n / min(w for w, _ in walls)})
+    av.avmp_profile_enable(p, False)
+    st = av.avmp_stats(p)
+    torch.cuda.synchronize()
+    av.avmp_pools_destroy(p)
+    del arena
+    torch.cuda.empty_cache()
+    return {"arena_GB": sc.arena_bytes / 1e9, "kv_pages_live": live, "kv_capacity_pages_at_start": sc.kv_capacity,
+            "placement": "live pages in the pool's highest slots: every vacated slot is live (worst case)",
+            "bound_pages_per_s": HBM_PEAK_GBPS * 1e9 / (2 * spec.kv_page_bytes),
+            "rows": rows, "migrations": st["migrations"], "units_copied": st["units_copied"]}
 
 
 def migration_compare(args, spec, sc, chunk):
@@ -242,6 +401,8 @@ def main():
                     help="replay the decode part of the step from a HIP graph captured once (churn "
                          "and migration stay eager; their table updates are flushed before each replay)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-capacity-sweep", action="store_true",
+                    help="skip the migration sweep on pools filling about 200 GB of HBM")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the second pass that brackets every kernel with HIP events")
     ap.add_argument("--fill-threads", type=int, default=16)
@@ -273,14 +434,7 @@ def main():
         return
 
     import numpy as np
-    import torch
-    from paper_2605_22416_amd import binding as av
     from gen import inputs
-    from paper_2605_22416_amd.session import DeviceSession
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
-        sys.exit(1)
 
     spec = inputs.JAMBA_MINI
     if args.state_dtype != "f32":
@@ -291,6 +445,23 @@ def main():
     args.batch = wl["batch"] if args.batch is None else args.batch
     args.seed = wl["seed"] if args.seed is None else args.seed
     sc = inputs.make_scenario(spec, args.workload, args.batch, args.seed, **wl["scenario"])
+    inp = inputs.step_inputs(spec, sc.batch, args.seed)
+    conv = inputs.conv_weights(spec, args.seed) if spec.conv_kernel else None
+    if not wl["fill"]:
+        args.no_cpu_baseline = True          # nothing to compare: the arena will hold zeros
+    # The oracle legs fork worker processes, so they run before this process touches the GPU.
+    base, ref_out = None, {}
+    if not args.no_cpu_baseline and not args.migration_compare:
+        base, ref_out = cpu_baseline(spec, sc, inp, args.seed, conv=conv,
+                                     others=args.workload == "uniform_short")
+
+    import torch
+    from paper_2605_22416_amd import binding as av
+    from paper_2605_22416_amd.session import DeviceSession
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        sys.exit(1)
     # SSM blocks count down from the top of the arena.  4 MiB blocks on 4 MiB boundaries measured
     # 87.1 us per SSM layer against 88.5 us at a 64 KiB-granular offset and 91.5 us at an odd
     # multiple of 2 MiB, so the arena's size is made a multiple of 4 MiB for them; 2 MiB blocks
@@ -315,33 +486,29 @@ def main():
     if args.migration_compare:
         print(json.dumps(migration_compare(args, spec, sc, vmm_chunk)))
         return
-    inp = inputs.step_inputs(spec, sc.batch, args.seed)
     t0 = time.perf_counter()
     ses = DeviceSession(sc, fill_byte=None if wl["fill"] else 0, vmm_chunk=vmm_chunk, remap=False)
     if wl["fill"]:
         ses.fill(threads=args.fill_threads)
-    else:
-        args.no_cpu_baseline = True          # nothing to compare: the arena holds zeros
     setup_s = time.perf_counter() - t0
     stream = torch.cuda.current_stream()
-    conv = inputs.conv_weights(spec, args.seed) if spec.conv_kernel else None
     st, keep, o, y = ses.prepare_step(inp, conv=conv)
 
-    # ---- correctness of the very first step against the oracle sample ----------------
-    base, parity = None, None
+    # ---- correctness of the very first step against the oracle, every request ----------
+    parity = None
     ses.launch(st, stream)
     torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
-        base, ref_o, ref_y = cpu_baseline(spec, sc, inp, args.seed, conv=conv)
+    if ref_out:
         o_h, y_h = o.cpu().numpy(), y.cpu().numpy()
         eo = ey = 0.0
-        for r in ref_o:
-            eo = max(eo, float((np.abs(o_h[:, r] - ref_o[r]).max(axis=-1)
-                                / np.maximum(np.abs(ref_o[r]).max(axis=-1), 1e-30)).max()))
-            ey = max(ey, float((np.abs(y_h[:, r] - ref_y[r]).max(axis=-1)
-                                / np.maximum(np.abs(ref_y[r]).max(axis=-1), 1e-30)).max()))
-        parity = {"requests": len(ref_o), "attention_max_rel_err": eo, "ssm_max_rel_err": ey,
+        for r, (ref_o, ref_y) in ref_out.items():
+            eo = max(eo, float((np.abs(o_h[:, r] - ref_o).max(axis=-1)
+                                / np.maximum(np.abs(ref_o).max(axis=-1), 1e-30)).max()))
+            ey = max(ey, float((np.abs(y_h[:, r] - ref_y).max(axis=-1)
+                                / np.maximum(np.abs(ref_y).max(axis=-1), 1e-30)).max()))
+        parity = {"requests": len(ref_out), "attention_max_rel_err": eo, "ssm_max_rel_err": ey,
                   "tolerance": 2e-3}
+        ref_out = None
         if eo > 2e-3 or ey > 2e-3:
             print("bench.py: GPU step disagrees with the oracle: %r" % parity, file=sys.stderr)
             sys.exit(1)
@@ -529,6 +696,12 @@ def main():
     av.avmp_profile_enable(ses.p, False)
     torch.cuda.synchronize()
     ses.close()
+    # ---- the capacity-scale migration sweep (pools filling about 200 GB), once the arena of
+    # ---- the decode benchmark is released ----------------------------------------------------
+    sweep_capacity = None
+    if args.workload == "uniform_short" and not args.no_capacity_sweep and args.backing == "plain":
+        torch.cuda.empty_cache()
+        sweep_capacity = capacity_migration_sweep(inputs.JAMBA_MINI, stream)
 
     out = {
         "metric": "hybrid_decode_step_achieved_hbm_GBps_batch%d" % sc.batch,
@@ -551,7 +724,8 @@ def main():
         "ms_per_step_with_kernel_events": (wall_ev / args.steps * 1e3) if wall_ev else None,
         "algorithmic_bytes_per_step": step_bytes,
         "migrated_pages_per_s": 2 * mig_pages * args.steps / wall,
-        "kernels": kernels, "migration_sweep": sweep, "churn": churn, "setup_s": setup_s,
+        "kernels": kernels, "migration_sweep": sweep, "migration_sweep_capacity": sweep_capacity,
+        "churn": churn, "setup_s": setup_s,
         "roofline": roofline, "roofline_attention": roofline_attention, "cpu_baseline": base,
         "parity_sample": parity,
     }

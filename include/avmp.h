@@ -199,8 +199,10 @@ int avmp_pools_destroy(avmp_pools_t* pools);
  * that writes a block itself must call avmp_flush first. n == 0: INVALID_ARG. */
 int avmp_alloc(avmp_pools_t* pools, int pool, uint32_t n, avmp_handle_t* out);
 
-/* Return n units (host array of handles, pools may be mixed).  Any stale,
- * duplicate or malformed handle: AVMP_ERR_INVALID_HANDLE, nothing freed. */
+/* The inverse of allocate() (Method, "Dynamic Pool Rebalancing": units return to
+ * the pool their handle's tag names; Fig. 1's table entry is unmapped).  Returns n
+ * units (host array of handles, pools may be mixed).  Any stale, duplicate or
+ * malformed handle: AVMP_ERR_INVALID_HANDLE, nothing freed. */
 int avmp_free(avmp_pools_t* pools, const avmp_handle_t* handles, uint32_t n);
 
 /* Capacity migration of Method, "Dynamic Pool Rebalancing": the donor pool
@@ -208,12 +210,27 @@ int avmp_free(avmp_pools_t* pools, const avmp_handle_t* handles, uint32_t n);
  * pool grows.  Live donor units in the vacated range are first copied on the
  * device to the best-ranked free slots below the new capacity and the table is
  * rewritten (handles stay valid).  All-or-nothing (the paper's rollback
- * clause): AVMP_ERR_CAPACITY if the donor has fewer than n free units. */
+ * clause): AVMP_ERR_CAPACITY if the donor has fewer than n free units.  The
+ * moves are planned straight into pinned memory and copied in slices of 2048
+ * units, each slice launched on `stream` while the host plans the next. */
 int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, void* stream,
                  avmp_migrate_result_t* out);
 
-/* One hybrid decode step (translation + paged GQA attention + SSM update) for
- * every layer of `step`, enqueued on `stream`.  Attention per (request r, query
+/* The bytes between the two pools belong to neither: what a migration left over
+ * (its wasted bytes, Method, "Dynamic Pool Rebalancing") and whatever the arena
+ * holds beyond the initial capacities.  avmp_absorb_gap gives `pool` every whole
+ * unit that fits into them: its capacity grows by gap / unit slots just above the
+ * old capacity, nothing is copied, nobody shrinks; the remainder stays in the gap
+ * and is reported as bytes_wasted (units_copied = 0).  Counted as a migration of
+ * zero donor bytes.  AVMP_ERR_CAPACITY, nothing changed, if the gap holds less than
+ * one unit.  Host only: the new capacity reaches the device with the next flush. */
+int avmp_absorb_gap(avmp_pools_t* pools, int pool, avmp_migrate_result_t* out);
+
+/* One hybrid decode step over both caches (Background, "KV Cache and SSM State
+ * Management": paged scatter-gather reads of the KV cache, in-place contiguous
+ * update of one SSM block per layer per sequence; handles resolved as in Fig. 1):
+ * translation + paged GQA attention + SSM update for every layer of `step`,
+ * enqueued on `stream`.  Attention per (request r, query
  * head j, g = j / (n_q_heads/n_kv_heads)): o = softmax_t(q.K_t[g]/sqrt(D)) . V[g]
  * over the ctx[r] resident tokens; SSM per (r, h, p, n): a = exp(dt*A),
  * S <- a*S + dt*x*B[n] in place, y = sum_n S*C[n] with the updated S (before it is
@@ -257,7 +274,14 @@ int avmp_workspace_info(const avmp_pools_t* pools, uint64_t* bytes, uint64_t* al
  * have passed since the last rebalance; REBALANCING -> BALANCED when the
  * migration completes; X_PRESSURED -> BALANCED when X's free fraction recovers.
  * One rebalance gives the starving pool up to migration_batch_size units
- * (limited by the donor's free units).  Defaults: 0.05, 0.30, 128, 1000. */
+ * (limited by the donor's free units).  When the gap between the pools already
+ * holds that many units the step takes them from there (avmp_absorb_gap): no donor
+ * is needed, so threshold_high is not consulted, but the step is throttled and
+ * counted like any other.  Defaults: 0.05, 0.30, 128, 1000.
+ * Where the paper's text and its Fig. 2 differ, Fig. 2 is followed: a failing
+ * allocation rebalances only if its own pool's free fraction is below
+ * threshold_low, and a failure in one pool is ignored while the machine waits in
+ * the other pool's PRESSURED state. */
 typedef struct avmp_policy {
   double threshold_low;
   double threshold_high;
@@ -286,15 +310,22 @@ int avmp_policy_state(const avmp_pools_t* pools, avmp_policy_state_t* out);
  * is full the state machine above may migrate capacity from the other pool (on
  * `stream`, as avmp_migrate) and the allocation is retried once.  With no donor
  * it behaves exactly as avmp_alloc (static partition).  *donor_units_migrated
- * (may be NULL) receives the number of units the other pool gave up, else 0. */
+ * (may be NULL) receives the number of units the other pool gave up (0 when
+ * nothing moved or the step came out of the gap).  It is written on every return,
+ * also when the retry still ends in AVMP_ERR_CAPACITY: the capacity has moved by
+ * then, as avmp_stats shows.  This is the one exception to "a failing call leaves
+ * every observable unchanged". */
 int avmp_alloc_auto(avmp_pools_t* pools, int pool, uint32_t n, avmp_handle_t* out, void* stream,
                     uint32_t* donor_units_migrated);
 
-/* Push queued table updates and zero fills to the device on `stream`. */
+/* Push queued table updates (Fig. 1's VirtualPageTable, mirrored on the device),
+ * pool capacities and zero fills of new SSM blocks to the device on `stream`. */
 int avmp_flush(avmp_pools_t* pools, void* stream);
 
-/* Device-side translation of n handles (device array) to byte offsets from the
- * arena base (device array, UINT64_MAX for handles that do not resolve). */
+/* Device-side translation (Fig. 1: pool tag selects the store, page id indexes
+ * the table, the entry is the physical slot) of n handles (device array) to byte
+ * offsets from the arena base (device array, UINT64_MAX for handles that do not
+ * resolve). */
 int avmp_translate(avmp_pools_t* pools, const avmp_handle_t* handles_dev, uint32_t n,
                    uint64_t* offsets_dev, void* stream);
 
@@ -303,10 +334,16 @@ int avmp_translate(avmp_pools_t* pools, const avmp_handle_t* handles_dev, uint32
 int avmp_resolve(const avmp_pools_t* pools, avmp_handle_t h, uint32_t* pool, uint32_t* slot,
                  uint64_t* byte_off);
 
+/* The allocator's counters (Method, "Dynamic Pool Rebalancing" and Evaluation:
+ * per-pool capacity and free units behind the free fractions of Fig. 2, the logical
+ * operation counter the throttle reads, capacity errors, migrations, migrated and
+ * wasted bytes). */
 int avmp_stats(const avmp_pools_t* pools, avmp_stats_t* out);
 
-/* Synchronise `stream`, then report and reset the number of handles that the
- * kernels could not translate (such pages/blocks are skipped, never touched). */
+/* Report and reset, in the order of `stream` (behind the kernels already queued on
+ * it), the number of handles that the kernels could not translate (such
+ * pages/blocks are skipped, never touched); returns after `stream` has drained.
+ * Not for use under graph capture. */
 int avmp_device_faults(avmp_pools_t* pools, void* stream, uint64_t* out);
 
 /* Per-kernel timing with HIP events on the launch stream.  While enabled, every

@@ -129,6 +129,7 @@ lib.avmp_alloc.argtypes = [_P, C.c_int, C.c_uint32, _P]
 lib.avmp_free.argtypes = [_P, _P, C.c_uint32]
 lib.avmp_migrate.argtypes = [_P, C.c_int, C.c_uint32, _P, C.POINTER(avmp_migrate_result_t)]
 lib.avmp_decode_step.argtypes = [_P, C.POINTER(avmp_step_t), _P]
+lib.avmp_absorb_gap.argtypes = [_P, C.c_int, C.POINTER(avmp_migrate_result_t)]
 lib.avmp_decode_step_noalloc.argtypes = [_P, C.POINTER(avmp_step_t), _P]
 lib.avmp_flush.argtypes = [_P, _P]
 lib.avmp_workspace_reserve.argtypes = [_P, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
@@ -156,7 +157,7 @@ for _f in ("avmp_geometry", "avmp_pools_create", "avmp_pools_destroy", "avmp_all
            "avmp_migrate", "avmp_decode_step", "avmp_flush", "avmp_translate", "avmp_resolve",
            "avmp_stats", "avmp_device_faults", "avmp_profile_enable", "avmp_profile_read",
            "avmp_policy_set", "avmp_policy_state", "avmp_alloc_auto", "avmp_workspace_reserve",
-           "avmp_workspace_info", "avmp_decode_step_noalloc"):
+           "avmp_workspace_info", "avmp_decode_step_noalloc", "avmp_absorb_gap"):
     getattr(lib, _f).restype = C.c_int
 
 
@@ -238,6 +239,12 @@ def avmp_free(pools, handles) -> int:
 def avmp_migrate(pools, donor_pool: int, n_donor_units: int, stream=None):
     res = avmp_migrate_result_t()
     rc = lib.avmp_migrate(pools, donor_pool, n_donor_units, _stream(stream), C.byref(res))
+    return rc, res
+
+
+def avmp_absorb_gap(pools, pool: int):
+    res = avmp_migrate_result_t()
+    rc = lib.avmp_absorb_gap(pools, pool, C.byref(res))
     return rc, res
 
 

@@ -131,12 +131,14 @@ struct avmp_pools {
   uint8_t* arena = nullptr;
   uint32_t* table_dev = nullptr;
   unsigned long long* faults_dev = nullptr;
+  unsigned long long* faults_host = nullptr;   // pinned: where avmp_device_faults reads the counter to
   float* ws = nullptr;                 // work buffer of the decode step (see WorkLayout)
   size_t ws_bytes = 0;
   uint64_t ws_allocations = 0;
   std::vector<void*> ws_retired;       // outgrown work buffers: a step in flight (or a captured
                                        // graph) may still name them, so they live until destroy
   std::vector<avmp::TableUpdate> pending;
+  bool pending_entries = false;        // `pending` holds table entries, not just the two capacities
   std::vector<uint32_t> pending_zero;  // SSM slots to clear
   Staging staging;
   avmp::Rebalancer rebalancer;
@@ -168,17 +170,24 @@ struct avmp_pools {
   }
   void prof_stop(int idx, hipStream_t s) { (void)hipEventRecord(prof[size_t(idx)].b, s); }
 
+  // the device table is followed by the two pool capacities, updated like table entries
+  size_t table_entries() const { return size_t(st.max_vid(0)) + st.max_vid(1); }
+  void queue_capacities() {   // does not count as a pending table entry
+    for (int pl = 0; pl < 2; ++pl)
+      pending.push_back({uint32_t(table_entries()) + uint32_t(pl), st.capacity(pl)});
+  }
+
   avmp::DevPools dev_view() const {
     avmp::DevPools P{};
     P.arena = arena;
     P.usable = st.geometry().usable;
     P.table = table_dev;
+    P.capacity = table_dev + table_entries();
     P.faults = faults_dev;
     for (int p = 0; p < 2; ++p) {
       P.unit[p] = st.geometry().unit[p];
       P.vid_base[p] = st.vid_base(p);
       P.max_vid[p] = st.max_vid(p);
-      P.capacity[p] = st.capacity(p);
     }
     return P;
   }
@@ -232,7 +241,7 @@ struct ProfScope {
 // Queue -> device: table entries (coalesced to the last value per index, so the
 // scatter has no ordering hazard) and zero fills of freshly allocated SSM blocks.
 int flush_pending(avmp_pools* p, hipStream_t s) {
-  if (p->dead) return fail(AVMP_ERR_DEVICE, "arena lost its mapping in a failed remap");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, "a device call failed half way through a migration: these pools can only be destroyed");
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
   if (p->pending.empty() && p->pending_zero.empty()) return AVMP_OK;
   std::vector<avmp::TableUpdate> upd;
@@ -262,6 +271,7 @@ int flush_pending(avmp_pools* p, hipStream_t s) {
   HIP_TRY(p->staging.release_after(b, s));
   p->pending.clear();
   p->pending_zero.clear();
+  p->pending_entries = false;
   return AVMP_OK;
 }
 
@@ -329,7 +339,7 @@ uint32_t roomy_pages(uint32_t max_pages) {
 int check_step(avmp_pools* p, const avmp_step_t* st, uint32_t* n_attn_out, uint32_t* n_ssm_out) {
   if (p == nullptr || st == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
-  if (p->dead) return fail(AVMP_ERR_DEVICE, "arena lost its mapping in a failed remap");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, "a device call failed half way through a migration: these pools can only be destroyed");
   if (st->n_layers != 0 && st->layer_kind == nullptr) return fail(AVMP_ERR_INVALID_ARG, "layer_kind");
   uint32_t n_attn = 0, n_ssm = 0;
   for (uint32_t i = 0; i < st->n_layers; ++i) {
@@ -542,14 +552,18 @@ int avmp_pools_create(const avmp_config_t* cfg, void* arena_dev, size_t arena_by
       return fail(AVMP_ERR_INVALID_ARG, "the arena's GPU must be the current device");
     }
     if (e == hipSuccess) (void)scratch_on_device(p->device, &e);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->table_dev), entries * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->table_dev), (entries + 2) * sizeof(uint32_t));
     if (e == hipSuccess) e = hipMemset(p->table_dev, 0xFF, entries * sizeof(uint32_t));
+    const uint32_t caps[2] = {p->st.capacity(0), p->st.capacity(1)};
+    if (e == hipSuccess) e = hipMemcpy(p->table_dev + entries, caps, sizeof caps, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->faults_dev), sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(p->faults_dev, 0, sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&p->faults_host), sizeof(unsigned long long), hipHostMallocDefault);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
       if (p->table_dev) (void)hipFree(p->table_dev);
       if (p->faults_dev) (void)hipFree(p->faults_dev);
+      if (p->faults_host) (void)hipHostFree(p->faults_host);
       delete p;
       return fail_hip(e, "avmp_pools_create");
     }
@@ -573,6 +587,7 @@ int avmp_pools_destroy(avmp_pools_t* p) {
     for (void* old : p->ws_retired) (void)hipFree(old);
     (void)hipFree(p->table_dev);
     (void)hipFree(p->faults_dev);
+    (void)hipHostFree(p->faults_host);
   }
   delete p;
   return AVMP_OK;
@@ -585,6 +600,7 @@ int avmp_alloc(avmp_pools_t* p, int pool, uint32_t n, avmp_handle_t* out) {
   std::vector<uint32_t> tmp((n < room ? n : room) + 1);
   const size_t upd0 = p->pending.size(), zero0 = p->pending_zero.size();
   const int rc = p->st.alloc(pool, n, out ? tmp.data() : nullptr, &p->pending, &p->pending_zero);
+  p->pending_entries = true;
   if (rc != AVMP_OK) {
     p->pending.resize(upd0);
     p->pending_zero.resize(zero0);
@@ -601,6 +617,7 @@ int avmp_alloc(avmp_pools_t* p, int pool, uint32_t n, avmp_handle_t* out) {
 int avmp_free(avmp_pools_t* p, const avmp_handle_t* handles, uint32_t n) {
   if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
   const int rc = p->st.free_units(handles, n, &p->pending);
+  p->pending_entries = true;
   if (rc != AVMP_OK) return fail(rc, rc == AVMP_ERR_INVALID_HANDLE ? "stale or malformed handle" : "bad n");
   if (!p->has_device) p->pending.clear();
   return AVMP_OK;
@@ -636,16 +653,36 @@ int avmp_alloc_auto(avmp_pools_t* p, int pool, uint32_t n, avmp_handle_t* out, v
   int rc = avmp_alloc(p, pool, n, out);
   if (rc != AVMP_ERR_CAPACITY) return rc;
   // the capacity-error handler: the only place where the state machine runs
-  const uint32_t donate = p->st.on_capacity_error(pool, &p->rebalancer);
-  if (donate != 0) {
-    const int mrc = avmp_migrate(p, 1 - pool, donate, stream, nullptr);
-    if (mrc != AVMP_OK) return mrc;       // cannot happen for a planned step; device errors only
-    p->st.rebalance_done(&p->rebalancer);
-    if (donor_units_migrated) *donor_units_migrated = donate;
-    rc = avmp_alloc(p, pool, n, out);
+  uint32_t donate = 0;
+  const avmp::PoolState::Step step = p->st.on_capacity_error(pool, &p->rebalancer, &donate);
+  if (step == avmp::PoolState::kStepNone) {
+    ++p->rebalancer.oom_events;
+    return rc;
   }
+  const int mrc = step == avmp::PoolState::kStepFromGap ? avmp_absorb_gap(p, pool, nullptr)
+                                                        : avmp_migrate(p, 1 - pool, donate, stream, nullptr);
+  if (mrc != AVMP_OK) return mrc;         // cannot happen for a planned step; device errors only
+  p->st.rebalance_done(&p->rebalancer);
+  if (donor_units_migrated) *donor_units_migrated = donate;
+  rc = avmp_alloc(p, pool, n, out);
   if (rc == AVMP_ERR_CAPACITY) ++p->rebalancer.oom_events;
   return rc;
+}
+
+int avmp_absorb_gap(avmp_pools_t* p, int pool, avmp_migrate_result_t* out) {
+  if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  uint32_t gain = 0;
+  uint64_t wasted = 0;
+  const int rc = p->st.absorb_gap(pool, &gain, &wasted);
+  if (rc != AVMP_OK)
+    return fail(rc, rc == AVMP_ERR_CAPACITY ? "the gap holds less than one unit of this pool" : "bad pool");
+  if (p->has_device) p->queue_capacities();
+  if (out) {
+    out->units_copied = 0;
+    out->recipient_gain = gain;
+    out->bytes_wasted = wasted;
+  }
+  return AVMP_OK;
 }
 
 int avmp_flush(avmp_pools_t* p, void* stream) {
@@ -656,50 +693,73 @@ int avmp_flush(avmp_pools_t* p, void* stream) {
 int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migrate_result_t* out) {
   if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (p->has_device && (donor == 0 || donor == 1) && n != 0) {
-    // queued zero fills and table entries refer to the geometry before the move
+  if (p->has_device && (donor == 0 || donor == 1) && n != 0 &&
+      (p->pending_entries || !p->pending_zero.empty())) {
+    // queued zero fills and table entries refer to the geometry before the move (the copy
+    // kernel rewrites entries in stream order; queued capacities alone can wait)
     const int rc = flush_pending(p, s);
     if (rc != AVMP_OK) return rc;
   }
-  std::vector<avmp::Move> moves;
-  std::vector<avmp::TableUpdate> remap;     // the copy kernel rewrites these entries itself
-  uint32_t gain = 0;
-  uint64_t wasted = 0;
-  const int rc = p->st.migrate(donor, n, &moves, &remap, &gain, &wasted);
+  const int rc = p->st.migrate_begin(donor, n);
   if (rc != AVMP_OK)
     return fail(rc, rc == AVMP_ERR_CAPACITY ? "donor has too few free units" : "bad donor or n");
-  if (p->has_device && p->remap != nullptr && p->remappable[donor]) {
-    if (!moves.empty()) {
-      // nothing may touch a range while its backing changes
-      HIP_TRY(hipDeviceSynchronize());
-      const avmp::Geometry& g = p->st.geometry();
-      const uint64_t unit = g.unit[donor];
-      for (const avmp::Move& m : moves) {
-        const hipError_t e = p->remap->exchange(p->st.byte_offset(donor, m.src_slot),
-                                                p->st.byte_offset(donor, m.dst_slot), unit);
+  // from here on nothing can fail but a HIP call
+  uint32_t moved = 0;
+  const bool exchange = p->has_device && p->remap != nullptr && p->remappable[donor];
+  if (p->has_device && !exchange) {
+    // The moves are planned straight into pinned memory, a slice at a time, and each slice's
+    // copy is launched before the next is planned: the device copies while the host plans.
+    // The copy kernel rewrites the table entries of the units it moves.
+    constexpr uint32_t kSlice = 2048;
+    Staging::Buf* b = nullptr;
+    avmp::Move* list = nullptr;
+    for (;;) {
+      if (b == nullptr) {                     // at most n units move: one list for the whole call
+        const hipError_t e = p->staging.acquire(size_t(n) * sizeof(avmp::Move), &b);
+        if (e != hipSuccess) {
+          p->dead = true;                     // the host tables are half way through a migration
+          return fail_hip(e, "avmp_migrate: pinned memory for the move list");
+        }
+        list = static_cast<avmp::Move*>(b->host);
+      }
+      const uint32_t k = p->st.migrate_moves(list + moved, kSlice);
+      if (k == 0) break;
+      {
+        ProfScope scope(p, p->profiling, AVMP_K_MIGRATE_COPY, s);
+        const hipError_t e = avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor, list + moved, k, s);
         if (e != hipSuccess) {
           p->dead = true;
-          return fail_hip(e, "avmp_migrate: exchanging the backing of two slots");
+          return fail_hip(e, "avmp_migrate: copy launch");
         }
       }
-      p->pending.insert(p->pending.end(), remap.begin(), remap.end());
-    }
-  } else if (p->has_device && !moves.empty()) {
-    const size_t bytes = moves.size() * sizeof(avmp::Move);
-    Staging::Buf* b = nullptr;
-    HIP_TRY(p->staging.acquire(bytes, &b));
-    std::memcpy(b->host, moves.data(), bytes);
-    // capacities in the view are already the new ones; the copy needs none of them
-    {
-      ProfScope scope(p, p->profiling, AVMP_K_MIGRATE_COPY, s);
-      HIP_TRY(avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor,
-                                        static_cast<const avmp::Move*>(b->host),
-                                        uint32_t(moves.size()), s));
+      moved += k;
     }
     HIP_TRY(p->staging.release_after(b, s));
+  } else {
+    std::vector<avmp::Move> moves(n);
+    for (uint32_t k; (k = p->st.migrate_moves(moves.data() + moved, n - moved)) != 0;) moved += k;
+    if (exchange && moved != 0) {
+      // nothing may touch a range while its backing changes
+      hipError_t e = hipDeviceSynchronize();
+      const uint64_t unit = p->st.geometry().unit[donor];
+      for (uint32_t i = 0; e == hipSuccess && i < moved; ++i)
+        e = p->remap->exchange(p->st.byte_offset(donor, moves[i].src_slot),
+                               p->st.byte_offset(donor, moves[i].dst_slot), unit);
+      if (e != hipSuccess) {
+        p->dead = true;
+        return fail_hip(e, "avmp_migrate: exchanging the backing of two slots");
+      }
+      for (uint32_t i = 0; i < moved; ++i)
+        p->pending.push_back({p->st.vid_base(donor) + moves[i].vid, moves[i].dst_slot});
+      p->pending_entries = true;
+    }
   }
+  uint32_t gain = 0;
+  uint64_t wasted = 0;
+  p->st.migrate_end(&gain, &wasted);
+  if (p->has_device) p->queue_capacities();   // reach the device with the next flush, before any kernel
   if (out) {
-    out->units_copied = uint32_t(moves.size());
+    out->units_copied = moved;
     out->recipient_gain = gain;
     out->bytes_wasted = wasted;
   }
@@ -879,12 +939,12 @@ int avmp_profile_read(avmp_pools_t* p, void* stream, avmp_profile_t* out) {
 int avmp_device_faults(avmp_pools_t* p, void* stream, uint64_t* out) {
   if (p == nullptr || out == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
+  // read and reset in stream order, behind the kernels already queued and ahead of later ones
   hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipMemcpyAsync(p->faults_host, p->faults_dev, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemsetAsync(p->faults_dev, 0, sizeof(unsigned long long), s));
   HIP_TRY(hipStreamSynchronize(s));
-  unsigned long long v = 0;
-  HIP_TRY(hipMemcpy(&v, p->faults_dev, sizeof(v), hipMemcpyDeviceToHost));
-  HIP_TRY(hipMemset(p->faults_dev, 0, sizeof(v)));
-  *out = v;
+  *out = *p->faults_host;
   return AVMP_OK;
 }
 

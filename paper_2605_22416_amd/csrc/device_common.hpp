@@ -1,6 +1,9 @@
 // Device-side view of the pools and handle translation (Fig. 1: the handle's
 // pool tag selects the store, its page id indexes the table, the table entry
 // is the physical slot).  Shared by every kernel; passed by value at launch.
+// Everything in it is fixed when the pools are created: what rebalancing changes
+// (table entries, pool capacities) lives in device memory behind its pointers, so
+// a launch recorded in a graph still sees the current values when replayed.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -13,11 +16,11 @@ struct DevPools {
   uint8_t* arena;                 // 128-byte aligned base
   uint64_t usable;                // SSM slots count down from arena + usable
   const uint32_t* table;          // [max_vid[0] + max_vid[1]]: vid -> slot, 0xFFFFFFFF unmapped
+  const uint32_t* capacity;       // [2]: slots each pool holds now (two words behind the table)
   unsigned long long* faults;     // handles that did not translate
   uint64_t unit[2];
   uint32_t vid_base[2];
   uint32_t max_vid[2];
-  uint32_t capacity[2];
 };
 
 constexpr uint32_t kDevUnmapped = 0xFFFFFFFFu;

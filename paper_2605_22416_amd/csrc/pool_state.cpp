@@ -52,6 +52,28 @@ int64_t MinBitset::min() const {
   return int64_t(idx);
 }
 
+int64_t MinBitset::next(uint64_t from) const {
+  const uint64_t n_leaf_bits = uint64_t(lv_[0].size()) << 6;
+  if (count_ == 0 || from >= n_leaf_bits) return -1;
+  // climb while the rest of the current word (at and above `from`) is empty, then descend
+  uint64_t idx = from;
+  size_t l = 0;
+  for (;;) {
+    const uint64_t w = lv_[l][idx >> 6] & (~0ull << (idx & 63));
+    if (w != 0) {
+      idx = (idx & ~63ull) | uint64_t(__builtin_ctzll(w));
+      break;
+    }
+    idx = (idx >> 6) + 1;                     // first word to the right, seen from the level above
+    if (++l == lv_.size() || idx >= (uint64_t(lv_[l].size()) << 6)) return -1;
+  }
+  while (l > 0) {
+    --l;
+    idx = (idx << 6) | uint64_t(__builtin_ctzll(lv_[l][idx]));
+  }
+  return int64_t(idx);
+}
+
 // ---------------------------------------------------------------------------
 // geometry
 // ---------------------------------------------------------------------------
@@ -170,49 +192,98 @@ int PoolState::free_units(const uint32_t* handles, uint32_t n, std::vector<Table
   return 0;
 }
 
-int PoolState::migrate(int donor, uint32_t n, std::vector<Move>* moves,
-                       std::vector<TableUpdate>* upd, uint32_t* gain_out, uint64_t* wasted_out) {
+int PoolState::migrate_begin(int donor, uint32_t n) {
   if ((donor != 0 && donor != 1) || n == 0) return 3;
   ++c_.ops;
   // all-or-nothing: checked before anything is touched, so "rollback" is trivial
   if (n > capacity_[donor] || free_rank_[donor].size() < n) return 1;
-  const int recip = 1 - donor;
   const uint32_t oldcap = capacity_[donor], newcap = oldcap - n;
   // free slots of the vacated high range leave the free set first ...
   for (uint32_t s = newcap; s < oldcap; ++s)
     if (vid_of_[donor][s] == kUnmapped) free_rank_[donor].erase(rank_of_[donor][s]);
-  // ... then each live unit there moves to the best-ranked free slot below newcap
-  for (uint32_t s = newcap; s < oldcap; ++s) {
-    uint32_t vid = vid_of_[donor][s];
+  mig_.donor = donor;
+  mig_.n = n;
+  mig_.oldcap = oldcap;
+  mig_.next_src = newcap;
+  mig_.moved = 0;
+  mig_.rank_cursor = 0;
+  return 0;
+}
+
+uint32_t PoolState::migrate_moves(Move* out, uint32_t max) {
+  const int donor = mig_.donor;
+  uint32_t k = 0;
+  // ... then each live unit there moves to the best-ranked free slot below the new capacity;
+  // successive best ranks only grow, so the search resumes where the last one ended
+  for (; mig_.next_src < mig_.oldcap && k < max; ++mig_.next_src) {
+    const uint32_t s = mig_.next_src;
+    const uint32_t vid = vid_of_[donor][s];
     if (vid == kUnmapped) continue;
-    uint32_t r = uint32_t(free_rank_[donor].min());
-    uint32_t dst = slot_at_[donor][r];
+    const uint32_t r = uint32_t(free_rank_[donor].next(mig_.rank_cursor));
+    mig_.rank_cursor = uint64_t(r) + 1;
+    const uint32_t dst = slot_at_[donor][r];
     free_rank_[donor].erase(r);
     vid_of_[donor][dst] = vid;
     vid_of_[donor][s] = kUnmapped;
     slot_of_[donor][vid] = dst;
-    moves->push_back({s, dst, vid});
-    upd->push_back({vid_base(donor) + vid, dst});
+    out[k++] = {s, dst, vid};
   }
-  capacity_[donor] = newcap;
-  uint64_t avail = gap_ + uint64_t(n) * g_.unit[donor];
+  mig_.moved += k;
+  return k;
+}
+
+void PoolState::migrate_end(uint32_t* gain_out, uint64_t* wasted_out) {
+  const int donor = mig_.donor, recip = 1 - donor;
+  capacity_[donor] = mig_.oldcap - mig_.n;
+  uint64_t avail = gap_ + uint64_t(mig_.n) * g_.unit[donor];
   uint32_t gain = uint32_t(avail / g_.unit[recip]);
   gap_ = avail % g_.unit[recip];
   for (uint32_t s = capacity_[recip]; s < capacity_[recip] + gain; ++s)
     free_rank_[recip].insert(rank_of_[recip][s]);
   capacity_[recip] += gain;
   ++c_.migrations;
-  c_.units_copied += moves->size();
-  c_.bytes_migrated += uint64_t(n) * g_.unit[donor];
+  c_.units_copied += mig_.moved;
+  c_.bytes_migrated += uint64_t(mig_.n) * g_.unit[donor];
   c_.bytes_wasted += gap_;
   *gain_out = gain;
+  *wasted_out = gap_;
+  mig_.donor = -1;
+}
+
+int PoolState::migrate(int donor, uint32_t n, std::vector<Move>* moves,
+                       std::vector<TableUpdate>* upd, uint32_t* gain_out, uint64_t* wasted_out) {
+  const int rc = migrate_begin(donor, n);
+  if (rc != 0) return rc;
+  Move buf[256];
+  for (uint32_t k; (k = migrate_moves(buf, 256)) != 0;)
+    for (uint32_t i = 0; i < k; ++i) {
+      moves->push_back(buf[i]);
+      upd->push_back({vid_base(donor) + buf[i].vid, buf[i].dst_slot});
+    }
+  migrate_end(gain_out, wasted_out);
+  return 0;
+}
+
+int PoolState::absorb_gap(int pool, uint32_t* gain_out, uint64_t* wasted_out) {
+  if (pool != 0 && pool != 1) return 3;
+  ++c_.ops;
+  const uint64_t gain = gap_ / g_.unit[pool];
+  if (gain == 0) return 1;
+  for (uint64_t s = capacity_[pool]; s < capacity_[pool] + gain; ++s)
+    free_rank_[pool].insert(rank_of_[pool][s]);
+  capacity_[pool] += uint32_t(gain);
+  gap_ -= gain * g_.unit[pool];
+  ++c_.migrations;
+  c_.bytes_wasted += gap_;
+  *gain_out = uint32_t(gain);
   *wasted_out = gap_;
   return 0;
 }
 
-uint32_t PoolState::on_capacity_error(int pool, Rebalancer* rb) const {
+PoolState::Step PoolState::on_capacity_error(int pool, Rebalancer* rb, uint32_t* donor_units_out) const {
   const Policy& pol = rb->policy;
   const int other = 1 - pool;
+  *donor_units_out = 0;
   auto free_fraction = [&](int p) {
     return capacity_[p] ? double(capacity_[p] - live_[p]) / double(capacity_[p]) : 0.0;
   };
@@ -221,18 +292,23 @@ uint32_t PoolState::on_capacity_error(int pool, Rebalancer* rb) const {
   if (rb->state == kKvPressured && free_fraction(0) >= pol.threshold_low) rb->state = kBalanced;
   if (rb->state == kSsmPressured && free_fraction(1) >= pol.threshold_low) rb->state = kBalanced;
   if (rb->state == kBalanced && free_fraction(pool) < pol.threshold_low) rb->state = pressured;
-  if (rb->state != pressured) return 0;
-  if (!(free_fraction(other) > pol.threshold_high)) return 0;       // no donor: static behaviour
-  if (rb->has_rebalanced && c_.ops - rb->last_rebalance_op < pol.min_rebalance_interval_ops)
-    return 0;                                                        // throttled
+  if (rb->state != pressured) return kStepNone;
   const uint64_t want = uint64_t(pol.migration_batch_size) * g_.unit[pool];
-  if (want <= gap_) return 0;
+  const bool from_gap = want <= gap_;         // bytes nobody owns already hold the step's units
+  if (!from_gap && !(free_fraction(other) > pol.threshold_high)) return kStepNone;   // no donor: static behaviour
+  if (rb->has_rebalanced && c_.ops - rb->last_rebalance_op < pol.min_rebalance_interval_ops)
+    return kStepNone;                                                // throttled
+  if (from_gap) {
+    rb->state = kRebalancing;
+    return kStepFromGap;
+  }
   uint64_t donor_units = (want - gap_ + g_.unit[other] - 1) / g_.unit[other];
   const uint64_t donor_free = capacity_[other] - live_[other];
   if (donor_units > donor_free) donor_units = donor_free;
-  if (donor_units == 0) return 0;
+  if (donor_units == 0) return kStepNone;
   rb->state = kRebalancing;
-  return uint32_t(donor_units);
+  *donor_units_out = uint32_t(donor_units);
+  return kStepMigrate;
 }
 
 void PoolState::rebalance_done(Rebalancer* rb) const {

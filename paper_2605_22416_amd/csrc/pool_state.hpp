@@ -25,6 +25,7 @@ class MinBitset {
   void erase(uint64_t i);
   bool contains(uint64_t i) const { return (lv_[0][i >> 6] >> (i & 63)) & 1; }
   int64_t min() const;               // -1 when empty
+  int64_t next(uint64_t from) const; // smallest member >= from, -1 if none
   uint64_t size() const { return count_; }
 
  private:
@@ -94,14 +95,27 @@ class PoolState {
   int free_units(const uint32_t* handles, uint32_t n, std::vector<TableUpdate>* upd);
   int migrate(int donor, uint32_t n, std::vector<Move>* moves, std::vector<TableUpdate>* upd,
               uint32_t* gain, uint64_t* wasted);
+  // The same migration in three steps, so that a caller can start copying the first moves
+  // while the rest is still being planned.  migrate_begin validates (all-or-nothing: after
+  // AVMP_OK nothing can fail) and takes the vacated range's free slots out of the free set;
+  // migrate_moves writes up to `max` further moves (ascending source slot) and returns how
+  // many, 0 once all live units of the vacated range have a new slot; migrate_end moves the
+  // capacity and updates the counters.  No other call may come between begin and end.
+  int migrate_begin(int donor, uint32_t n);
+  uint32_t migrate_moves(Move* out, uint32_t max);
+  void migrate_end(uint32_t* gain, uint64_t* wasted);
+  // The whole units of `pool` that fit into the gap between the pools go to it: no donor,
+  // no copy.  1 (capacity) if the gap holds less than one unit.
+  int absorb_gap(int pool, uint32_t* gain, uint64_t* wasted);
   bool resolve(uint32_t h, uint32_t* pool, uint32_t* slot, uint64_t* off) const;
 
   // The CapacityError handler of allocate(): runs the state machine for a failed
-  // allocation in `pool` and returns how many units the OTHER pool should donate
-  // now (0: no donor above threshold_high, throttled, or not pressured).  When it
-  // returns non-zero the state is kRebalancing; call rebalance_done() after the
-  // migration.
-  uint32_t on_capacity_error(int pool, Rebalancer* rb) const;
+  // allocation in `pool` and says what to do now.  kStepNone: nothing (not pressured,
+  // no donor above threshold_high, throttled).  kStepMigrate: the OTHER pool donates
+  // *donor_units.  kStepFromGap: the gap already holds the step's units, absorb it.
+  // For the last two the state is kRebalancing; call rebalance_done() after the move.
+  enum Step { kStepNone = 0, kStepMigrate = 1, kStepFromGap = 2 };
+  Step on_capacity_error(int pool, Rebalancer* rb, uint32_t* donor_units) const;
   void rebalance_done(Rebalancer* rb) const;
 
   uint64_t byte_offset(int pool, uint32_t slot) const {
@@ -126,6 +140,11 @@ class PoolState {
   MinBitset free_rank_[kPools];               // ranks of free slots below capacity
   MinBitset free_vid_[kPools];
   Counters c_;
+  struct {                                    // a migration between begin and end
+    int donor = -1;
+    uint32_t n = 0, next_src = 0, oldcap = 0, moved = 0;
+    uint64_t rank_cursor = 0;                 // every free rank below it has been taken
+  } mig_;
 };
 
 }  // namespace avmp

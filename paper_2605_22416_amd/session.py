@@ -131,6 +131,7 @@ class DeviceSession:
         if self.vmm is not None:
             av.avmp_vmm_arena_destroy(self.vmm)
             self.vmm = None
+        self.arena = None                      # the device memory goes back to torch
 
     # ---- unit access by handle (host resolve + a slice of the arena tensor) ----
     def unit_range(self, h: int):

@@ -48,10 +48,19 @@ int main(int argc, char** argv) {
       uint32_t out[8];
       int rc = st.alloc(pool, n, out, &upd, &zero);
       if (rc == 1) {
-        const uint32_t donate = st.on_capacity_error(pool, &rb);
-        if (donate) {
+        uint32_t donate = 0;
+        const PoolState::Step step_kind = st.on_capacity_error(pool, &rb, &donate);
+        if (step_kind != PoolState::kStepNone) {
           uint32_t gain; uint64_t wasted;
-          REQUIRE(st.migrate(1 - pool, donate, &moves, &upd, &gain, &wasted) == 0);
+          if (step_kind == PoolState::kStepFromGap) {
+            REQUIRE(st.absorb_gap(pool, &gain, &wasted) == 0);
+          } else {
+            // planned in slices, as the library does it
+            REQUIRE(st.migrate_begin(1 - pool, donate) == 0);
+            Move buf[3];
+            for (uint32_t k; (k = st.migrate_moves(buf, 3)) != 0;) moves.insert(moves.end(), buf, buf + k);
+            st.migrate_end(&gain, &wasted);
+          }
           st.rebalance_done(&rb);
           rc = st.alloc(pool, n, out, &upd, &zero);
         }
@@ -71,6 +80,10 @@ int main(int argc, char** argv) {
       }
       REQUIRE(st.free_units(hs, k, &upd) == 0);
       REQUIRE(st.free_units(hs, 1, &upd) == 2);          // stale now
+    } else if (u < 91) {
+      uint32_t gain; uint64_t wasted;
+      const int rc = st.absorb_gap(pool, &gain, &wasted);
+      REQUIRE(rc == 0 || rc == 1);
     } else if (u < 97) {
       uint32_t gain; uint64_t wasted;
       const int rc = st.migrate(pool, 1 + rng() % 6, &moves, &upd, &gain, &wasted);

@@ -345,6 +345,74 @@ def test_decode_step_replayed_from_a_hip_graph_matches_eager_steps():
     graphed.close()
 
 
+def test_graph_replay_after_a_migration_sees_the_new_capacities():
+    """A step captured in a HIP graph stays valid when capacity moves afterwards: a
+    migration gives the SSM pool new slots, one request's blocks move into them, and
+    the replayed graph (same handle buffers, new contents) must resolve the new
+    handles like an eager step on a twin session does."""
+    import torch
+    from paper_2605_22416_amd import binding as av
+    gh = _harness()
+    spec = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    ctx = [90, 300, 33]
+    sc = inputs.make_scenario(spec, "uniform_short", len(ctx), seed=14, ctx=ctx, permute=False)
+    # SSM pool exactly full, KV pool with 64 pages to spare (= one 4 MiB block of capacity)
+    sc.ssm_capacity = len(ctx) * spec.n_ssm
+    sc.kv_capacity = int(sc.n_pages.sum()) * spec.n_attn + 7 * 64
+    sc.arena_bytes = sc.kv_capacity * spec.kv_page_bytes + sc.ssm_capacity * spec.ssm_block_bytes
+    sc.slot_rank = [None, None]
+    inp = inputs.step_inputs(spec, len(ctx), seed=14)
+    twins = [gh.GpuPools(sc), gh.GpuPools(sc)]
+    for t in twins:
+        t.fill()
+    (eager, graphed) = twins
+    st_e, keep_e, o_e, y_e = eager.prepare_step(inp)
+    st_g, keep_g, o_g, y_g = graphed.prepare_step(inp)
+    eager.launch(st_e)
+    graphed.launch(st_g)
+    torch.cuda.synchronize()
+    assert torch.equal(o_e, o_g) and torch.equal(y_e, y_g)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        g.capture_begin()
+        rc = av.avmp_decode_step(graphed.p, st_g, side)
+        g.capture_end()
+    assert rc == av.AVMP_OK, av.avmp_last_error()
+    torch.cuda.synchronize()
+    old_cap = av.avmp_stats(graphed.p)["capacity"][1]
+    for t in twins:
+        # 7 x 64 pages of KV capacity become 7 blocks; request 0 takes them and gives its old ones back
+        rc, res = av.avmp_migrate(t.p, av.AVMP_POOL_KV, 7 * 64)
+        assert rc == av.AVMP_OK and res.recipient_gain == 7
+        rc, fresh = av.avmp_alloc(t.p, av.AVMP_POOL_SSM, spec.n_ssm)
+        assert rc == av.AVMP_OK
+        slots = [av.avmp_resolve(t.p, int(h))[2] for h in fresh]
+        assert min(slots) >= old_cap, "the new blocks must sit in the slots the migration added"
+        assert av.avmp_flush(t.p) == av.AVMP_OK                    # zero fills first, then the contents
+        torch.cuda.synchronize()
+        old = t.ssm[:, 0].copy()
+        for ls in range(spec.n_ssm):
+            t.write_unit(int(fresh[ls]), t.read_unit(int(old[ls])))
+        assert av.avmp_free(t.p, old) == av.AVMP_OK
+        t.ssm[:, 0] = fresh
+        t.ssm_dev.copy_(gh.to_dev(t.ssm))                          # same device buffer the graph names
+        assert av.avmp_flush(t.p) == av.AVMP_OK
+    torch.cuda.synchronize()
+    for it in range(3):
+        g.replay()
+        eager.launch(st_e)
+        torch.cuda.synchronize()
+        assert torch.isfinite(y_g).all()
+        assert torch.equal(o_e, o_g) and torch.equal(y_e, y_g), "replay %d differs" % it
+    assert av.avmp_device_faults(graphed.p) == (av.AVMP_OK, 0)
+    assert av.avmp_device_faults(eager.p) == (av.AVMP_OK, 0)
+    for ls in range(spec.n_ssm):
+        assert np.array_equal(eager.states(ls), graphed.states(ls))
+    eager.close()
+    graphed.close()
+
+
 @pytest.mark.parametrize("backing", BACKINGS)
 def test_alloc_auto_rebalances_on_device_and_keeps_contents(backing):
     """A capacity error in the KV pool with slack in the SSM pool: the handler

@@ -105,7 +105,7 @@ def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops):
     op = orc.Pools(helpers.oracle_shape(spec), arena, kv_cap, ssm_cap, slot_rank=ranks, with_data=False)
     lp = _lib_pools(spec, arena, kv_cap, ssm_cap, ranks)
     live = {0: [], 1: []}
-    n_cap = n_mig = n_bad = 0
+    n_cap = n_mig = n_bad = n_gap = 0
     for step in range(n_ops):
         u = rng.random()
         pool = int(rng.integers(0, 2))
@@ -136,8 +136,13 @@ def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops):
                 n_bad += 1
         elif u < 0.97:
             n = int(rng.integers(1, 7))
-            ores = op.migrate(pool, n)
-            lc, lres = av.avmp_migrate(lp, pool, n)
+            if rng.random() < 0.15:                        # the gap's whole units to one pool
+                ores = op.absorb_gap(pool)
+                lc, lres = av.avmp_absorb_gap(lp, pool)
+                n_gap += lc == av.AVMP_OK
+            else:
+                ores = op.migrate(pool, n)
+                lc, lres = av.avmp_migrate(lp, pool, n)
             assert lc == ores.code
             if lc == av.AVMP_OK:
                 n_mig += 1
@@ -146,13 +151,14 @@ def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops):
         else:
             assert av.avmp_alloc(lp, 2, 1)[0] == op.alloc(2, 1)[0] == orc.ERR_INVALID_ARG
             assert av.avmp_migrate(lp, pool, 0)[0] == op.migrate(pool, 0).code == orc.ERR_INVALID_ARG
+            assert av.avmp_absorb_gap(lp, 2)[0] == op.absorb_gap(2).code == orc.ERR_INVALID_ARG
         if step % 50 == 0:
             _check_same(op, lp)
             for h in live[0] + live[1]:
                 rc, pl, sl, off = av.avmp_resolve(lp, h)
                 assert rc == av.AVMP_OK and (pl, sl, off) == op.resolve(h)
     _check_same(op, lp)
-    assert n_cap > 100 and n_mig > 100 and n_bad > 50
+    assert n_cap > 100 and n_mig > 100 and n_bad > 50 and n_gap > 5
     assert av.avmp_resolve(lp, 0xFFFFFFFF)[0] == av.AVMP_ERR_INVALID_HANDLE
     av.avmp_pools_destroy(lp)
 

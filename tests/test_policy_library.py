@@ -137,3 +137,28 @@ def test_trace_driver_dynamic_split_has_fewest_capacity_errors_across_workloads(
     # and it never does worse than the split it started from
     for workload in ("uniform_short", "mixed_long", "agentic_burst"):
         assert per[(workload, "dynamic")] <= 1.1 * per[(workload, "static 0.5")], per
+
+
+def test_a_step_out_of_the_gap_matches_the_oracle():
+    """An arena larger than the two pools: the first capacity error is served from the
+    gap (no donor exists), the following ones are throttled, then the static behaviour."""
+    spec = inputs.TINY
+    kv_cap, ssm_cap = 10, 10
+    arena = kv_cap * spec.kv_page_bytes + ssm_cap * spec.ssm_block_bytes + 5 * spec.kv_page_bytes + 4096
+    policy = dict(threshold_low=0.05, threshold_high=0.30, migration_batch_size=4, min_rebalance_interval_ops=25)
+    op = orc.Pools(helpers.oracle_shape(spec), arena, kv_cap, ssm_cap, with_data=False)
+    cfg, keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
+                               spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, kv_cap, ssm_cap)
+    rc, lp = av.avmp_pools_create(cfg, None, arena)
+    assert rc == av.AVMP_OK and av.avmp_policy_set(lp, **policy) == av.AVMP_OK
+    rb = orc.Rebalancer(op, orc.Policy(**policy))
+    calls = [(0, 10), (1, 9), (0, 2), (0, 3)] + [(0, 1)] * 40
+    for pool, n in calls:
+        oc, oh, om = rb.allocate(pool, n)
+        lc, lh, lm = av.avmp_alloc_auto(lp, pool, n)
+        assert (oc, om) == (lc, lm) and (oc != orc.OK or list(lh) == oh)
+        assert av.avmp_stats(lp) == op.stats()
+        st = av.avmp_policy_state(lp)
+        assert (st["state"], st["rebalance_count"], st["oom_events"]) == (rb.state, rb.rebalance_count, rb.oom_events)
+    assert av.avmp_stats(lp)["capacity"] == (15, 10) and rb.rebalance_count == 1 and rb.oom_events > 30
+    av.avmp_pools_destroy(lp)
