@@ -211,8 +211,8 @@ int avmp_free(avmp_pools_t* pools, const avmp_handle_t* handles, uint32_t n);
  * device to the best-ranked free slots below the new capacity and the table is
  * rewritten (handles stay valid).  All-or-nothing (the paper's rollback
  * clause): AVMP_ERR_CAPACITY if the donor has fewer than n free units.  The
- * moves are planned straight into pinned memory and copied in slices of 2048
- * units, each slice launched on `stream` while the host plans the next. */
+ * moves are planned straight into pinned memory and copied in slices (1024 units,
+ * then 2048, 4096 and 8192), each launched on `stream` while the host plans the next. */
 int avmp_migrate(avmp_pools_t* pools, int donor_pool, uint32_t n_donor_units, void* stream,
                  avmp_migrate_result_t* out);
 

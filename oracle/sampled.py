@@ -23,8 +23,16 @@ def oracle_shape(spec) -> orc.Shape:
 class RequestReference:
     """One request of a scenario, rebuilt in its own small pools."""
 
-    def __init__(self, spec, seed: int, r: int, ctx: int, fresh: bool = False, scale_inputs=None):
+    def __init__(self, spec, seed: int, r: int, ctx: int, fresh: bool = False, scale_inputs=None,
+                 attn_ordinals=None, ssm_ordinals=None):
+        """spec may hold fewer layers than the scenario's model: attn_ordinals / ssm_ordinals
+        then say which of the model's attention / SSM layers (by ordinal among their kind)
+        the reference's layers stand for, i.e. whose unit contents they are filled with
+        (default: the first ones).  step() must be given inputs cut to the same layers."""
         self.spec, self.r = spec, r
+        ao = list(range(spec.n_attn)) if attn_ordinals is None else list(attn_ordinals)
+        so = list(range(spec.n_ssm)) if ssm_ordinals is None else list(ssm_ordinals)
+        assert len(ao) == spec.n_attn and len(so) == spec.n_ssm
         n_pages = -(-int(ctx) // spec.page_tokens)
         kv_cap = max(1, n_pages * spec.n_attn)
         ssm_cap = max(1, spec.n_ssm)
@@ -41,11 +49,11 @@ class RequestReference:
         for la in range(spec.n_attn):
             for i in range(n_pages):
                 self.pools.unit_view(int(self.kv[la, 0, i]))[:] = inputs.unit_content(
-                    spec, seed, inputs.POOL_KV, la, r, i, scale_inputs=scale_inputs)
+                    spec, seed, inputs.POOL_KV, ao[la], r, i, scale_inputs=scale_inputs)
         if not fresh:
             for ls in range(spec.n_ssm):
                 self.pools.unit_view(int(self.ssm[ls, 0]))[:] = inputs.unit_content(
-                    spec, seed, inputs.POOL_SSM, ls, r, 0, scale_inputs=scale_inputs)
+                    spec, seed, inputs.POOL_SSM, so[ls], r, 0, scale_inputs=scale_inputs)
 
     def step(self, inp, conv=None):
         """inp: the whole batch's step inputs; conv: (taps, bias) of the short convolution
@@ -61,3 +69,8 @@ class RequestReference:
 
     def state(self, layer: int) -> np.ndarray:
         return self.pools.state_values(int(self.ssm[layer, 0]))
+
+    def load_block(self, layer: int, raw: np.ndarray) -> None:
+        """Replace the bytes of this request's block of one SSM layer (e.g. by what the
+        other side has stored, so that the next step starts from the same state)."""
+        self.pools.unit_view(int(self.ssm[layer, 0]))[:] = np.asarray(raw, dtype=np.uint8)

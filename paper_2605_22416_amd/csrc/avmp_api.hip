@@ -710,7 +710,9 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
     // The moves are planned straight into pinned memory, a slice at a time, and each slice's
     // copy is launched before the next is planned: the device copies while the host plans.
     // The copy kernel rewrites the table entries of the units it moves.
-    constexpr uint32_t kSlice = 2048;
+    // Slices grow (1024, 2048, 4096, ... up to 8192 moves): the first copy starts early, the
+    // later ones are long enough to run at full rate.
+    uint32_t slice = 1024;
     Staging::Buf* b = nullptr;
     avmp::Move* list = nullptr;
     for (;;) {
@@ -722,8 +724,9 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
         }
         list = static_cast<avmp::Move*>(b->host);
       }
-      const uint32_t k = p->st.migrate_moves(list + moved, kSlice);
+      const uint32_t k = p->st.migrate_moves(list + moved, slice);
       if (k == 0) break;
+      if (slice < 8192) slice *= 2;
       {
         ProfScope scope(p, p->profiling, AVMP_K_MIGRATE_COPY, s);
         const hipError_t e = avmp::launch_migrate_copy(p->dev_view(), p->table_dev, donor, list + moved, k, s);

@@ -58,20 +58,24 @@ __global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t*
   const uint64_t unit = P.unit[pool];
   const uint64_t so = pool == 0 ? uint64_t(mv.src_slot) * unit : P.usable - (uint64_t(mv.src_slot) + 1) * unit;
   const uint64_t dof = pool == 0 ? uint64_t(mv.dst_slot) * unit : P.usable - (uint64_t(mv.dst_slot) + 1) * unit;
-  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(P.arena + so);
-  uint4* __restrict__ dst = reinterpret_cast<uint4*>(P.arena + dof);
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4* __restrict__ src = reinterpret_cast<const u32x4*>(P.arena + so);
+  u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(P.arena + dof);
   const uint64_t n16 = unit / 16;
   const uint64_t stride = uint64_t(gridDim.x) * 256;
   uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x;
-  // four independent 16-byte loads in flight per lane
+  // four independent 16-byte loads in flight per lane; every byte is touched once, so both
+  // directions carry the non-temporal hint
   for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    dst[i] = a;
-    dst[i + stride] = b;
-    dst[i + 2 * stride] = c;
-    dst[i + 3 * stride] = d;
+    const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                c = __builtin_nontemporal_load(src + i + 2 * stride),
+                d = __builtin_nontemporal_load(src + i + 3 * stride);
+    __builtin_nontemporal_store(a, dst + i);
+    __builtin_nontemporal_store(b, dst + i + stride);
+    __builtin_nontemporal_store(c, dst + i + 2 * stride);
+    __builtin_nontemporal_store(d, dst + i + 3 * stride);
   }
-  for (; i < n16; i += stride) dst[i] = src[i];
+  for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
   if (blockIdx.x == 0 && threadIdx.x == 0) table[P.vid_base[pool] + mv.vid] = mv.dst_slot;
 }
 

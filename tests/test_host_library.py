@@ -163,6 +163,36 @@ def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops):
     av.avmp_pools_destroy(lp)
 
 
+def test_capacity_scale_workload_cut_to_a_sixteenth_matches_the_oracle():
+    """The capacity-scale workload's shape at a sixteenth of its size (32 requests of
+    U[1024,8192] tokens and one of 16384, pools at 1.7x demand, seeded placement), where
+    the oracle's linear scans still finish: every allocation, then migration batches of 4,
+    64 and 1024 pages (a sixteenth of 64, 1024 and 16384), handle by handle."""
+    spec = inputs.JAMBA_MINI
+    rng = np.random.default_rng(1005)
+    ctx = np.concatenate([rng.integers(1024, 8193, size=32), [16384]]).astype(np.uint32)
+    sc = inputs.make_scenario(spec, "capacity", len(ctx), seed=1005, ctx=ctx, headroom=1.7)
+    op, kv, ssm = helpers.build_oracle(sc, with_data=False)
+    lp = _lib_pools(spec, sc.arena_bytes, sc.kv_capacity, sc.ssm_capacity, sc.slot_rank)
+    for pool, n, tag in helpers.alloc_order(sc):
+        lc, lh = av.avmp_alloc(lp, pool, n)
+        assert lc == av.AVMP_OK
+        want = kv[tag[1], tag[2], :n] if tag[0] == "kv" else ssm[:, tag[1]]
+        assert np.array_equal(lh, want)
+    _check_same(op, lp)
+    handles = np.concatenate([kv[kv != 0xFFFFFFFF], ssm.reshape(-1)])
+    for n in (4, 64, 1024):
+        ores = op.migrate(0, n)
+        lc, lres = av.avmp_migrate(lp, 0, n)
+        assert lc == ores.code == orc.OK
+        assert (lres.units_copied, lres.recipient_gain, lres.bytes_wasted) == \
+            (ores.units_copied, ores.recipient_gain, ores.bytes_wasted) and ores.units_copied > 0
+        _check_same(op, lp)
+        for h in handles[:: 7]:
+            assert av.avmp_resolve(lp, int(h))[1:] == op.resolve(int(h))
+    av.avmp_pools_destroy(lp)
+
+
 def test_jamba_shaped_allocation_order_matches_the_oracle():
     spec = inputs.scaled_down(inputs.JAMBA_MINI, 1)
     sc = inputs.make_scenario(spec, "uniform_short", 16, seed=1002)
