@@ -104,7 +104,7 @@ def write_traffic(fetch_csv, write_csv, batch, workload, seed):
                                 "fetch_bytes": int(round(c["FETCH_SIZE"])), "write_bytes": int(round(c["WRITE_SIZE"])),
                                 "kernels": list(KERNEL_MATCH[kind]), "source_sha256_16": source_digest(kind)}
     out["command"] = ("rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o f -- python3 bench.py "
-                      "--no-cpu-baseline --no-kernel-events --steps 4 --warmup 1   (and the same with "
+                      "--no-cpu-baseline --no-capacity-sweep --no-kernel-events --steps 4 --warmup 1   (and the same with "
                       "WRITE_SIZE); then python3 bench.py --write-traffic <f_counter_collection.csv> "
                       "<w_counter_collection.csv>")
     with open(TRAFFIC_FILE, "w") as f:

@@ -39,6 +39,7 @@ class ModelSpec:
     state_dtype: str = "f32"        # storage type of the SSM state in its block: "f32" or "bf16"
     conv_kernel: int = 0            # taps of the short convolution in front of the recurrence;
                                     # 0 = the block holds the recurrent state alone
+    pad_ssm_to_kv_page: bool = False  # unified-pool sizing: the block padded to whole KV pages
 
     @property
     def state_bytes(self) -> int:
@@ -74,8 +75,15 @@ class ModelSpec:
         return (self.conv_kernel - 1) * self.conv_dim * self.elem_bytes if self.conv_kernel else 0
 
     @property
-    def ssm_block_bytes(self) -> int:
+    def ssm_native_bytes(self) -> int:
         return (self.ssm_state_bytes + self.conv_window_bytes + 15) // 16 * 16
+
+    @property
+    def ssm_block_bytes(self) -> int:
+        n = self.ssm_native_bytes
+        if self.pad_ssm_to_kv_page:
+            n = -(-n // self.kv_page_bytes) * self.kv_page_bytes
+        return n
 
 
 # one attention + one SSM layer, fp32, 4 query / 2 KV heads x 64, SSM 4 x 32 x 16
@@ -96,6 +104,11 @@ def scaled_down(spec: ModelSpec, n_blocks: int = 1, name: Optional[str] = None) 
 def with_conv(spec: ModelSpec, conv_kernel: int = 4) -> ModelSpec:
     """Same model whose SSM blocks also hold the last conv_kernel-1 inputs of the short convolution."""
     return replace(spec, name=spec.name + "_conv%d" % conv_kernel, conv_kernel=conv_kernel)
+
+
+def with_padded_blocks(spec: ModelSpec) -> ModelSpec:
+    """Same model with every SSM block padded up to a whole number of KV pages."""
+    return replace(spec, name=spec.name + "_padded", pad_ssm_to_kv_page=True)
 
 
 def with_state_dtype(spec: ModelSpec, state_dtype: str) -> ModelSpec:
@@ -264,7 +277,7 @@ def unit_content(spec: ModelSpec, seed: int, pool: int, layer: int, request: int
         s = 1.0 / math.sqrt(spec.head_dim) if sc else 1.0
         n = spec.kv_page_bytes // spec.elem_bytes
         return elements(rng, n, s, spec.dtype).view(np.uint8)
-    if not spec.conv_kernel:
+    if not spec.conv_kernel and not spec.pad_ssm_to_kv_page:
         n = spec.ssm_block_bytes // spec.state_bytes
         return elements(rng, n, 1.0, spec.state_dtype).view(np.uint8)
     # recurrent state, then the window of the last K-1 convolution inputs [K-1][conv_dim]
@@ -273,9 +286,10 @@ def unit_content(spec: ModelSpec, seed: int, pool: int, layer: int, request: int
     out = np.zeros(spec.ssm_block_bytes, dtype=np.uint8)
     n = spec.ssm_state_bytes // spec.state_bytes
     out[: spec.ssm_state_bytes] = elements(rng, n, 1.0, spec.state_dtype).view(np.uint8)
-    m = (spec.conv_kernel - 1) * spec.conv_dim
-    out[spec.ssm_state_bytes: spec.ssm_state_bytes + spec.conv_window_bytes] = \
-        elements(rng, m, s, spec.dtype).view(np.uint8)
+    if spec.conv_kernel:
+        m = (spec.conv_kernel - 1) * spec.conv_dim
+        out[spec.ssm_state_bytes: spec.ssm_state_bytes + spec.conv_window_bytes] = \
+            elements(rng, m, s, spec.dtype).view(np.uint8)
     return out
 
 

@@ -98,6 +98,11 @@ typedef struct avmp_config {
                                       as [K-1][H*P + 2*N] elements (oldest first), and a step takes
                                       xbc / conv_taps / conv_bias instead of x, B, C.  Needs H*P and
                                       N to be multiples of 16/element_bytes */
+  uint32_t ssm_pad_to_kv_page;     /* 0 (default): the block has its native size.  1: the sizing of a
+                                      unified pool (Background, "Existing Cache Management"; the
+                                      padded_unified baseline of Evaluation, "Experimental Setup"):
+                                      the block is padded up to a whole number of KV pages.  Only the
+                                      unit size changes; avmp_geometry reports both sizes */
   uint32_t kv_capacity;            /* initial KV pool capacity in pages */
   uint32_t ssm_capacity;           /* initial SSM pool capacity in blocks */
   uint32_t max_vid[2];             /* virtual ids per pool; 0 = as many as slots could ever exist */
@@ -107,7 +112,9 @@ typedef struct avmp_config {
 } avmp_config_t;
 
 typedef struct avmp_geometry {
-  uint64_t unit_bytes[2];          /* KV page bytes, SSM block bytes (rounded up to 16) */
+  uint64_t unit_bytes[2];          /* KV page bytes, SSM block bytes (rounded up to 16; with
+                                      ssm_pad_to_kv_page to a multiple of the KV page) */
+  uint64_t ssm_native_bytes;       /* SSM block bytes without that padding */
   uint64_t usable_bytes;
   uint32_t max_slots[2];           /* usable_bytes / unit_bytes[pool] */
 } avmp_geometry_t;

@@ -93,6 +93,9 @@ class Shape:
     state_dtype: str = "f32"   # storage type of the SSM state (bytes_per_element of the block)
     conv_kernel: int = 0       # K taps of the short causal convolution in front of the
                                # recurrence; 0 = the block is the recurrent state alone
+    pad_ssm_to_kv_page: bool = False   # sizing of a unified pool (Background, "Existing Cache
+                               # Management"; Evaluation, the padded_unified baseline): the SSM
+                               # block is padded up to a whole number of attention pages
 
     @property
     def conv_dim(self) -> int:
@@ -122,7 +125,16 @@ class Shape:
             raw = self.state_dim * self.state_bytes    # state_dim x bytes_per_element
             if self.conv_kernel:                       # + the last K-1 convolution inputs
                 raw += (self.conv_kernel - 1) * self.conv_dim * self.elem_bytes
-        return round_up(raw, PAGE_ALIGN)
+        unit = round_up(raw, PAGE_ALIGN)
+        if pool == POOL_SSM and self.pad_ssm_to_kv_page:
+            unit = round_up(unit, self.unit_bytes(POOL_KV))
+        return unit
+
+    def native_ssm_bytes(self) -> int:
+        """What the block holds without the unified-pool padding."""
+        return Shape(self.dtype, self.page_tokens, self.n_q_heads, self.n_kv_heads, self.head_dim,
+                     self.ssm_heads, self.ssm_headdim, self.ssm_dstate, self.state_dtype,
+                     self.conv_kernel).unit_bytes(POOL_SSM)
 
 
 def decode_elements(raw: np.ndarray, dtype: str) -> np.ndarray:

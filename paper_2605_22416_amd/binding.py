@@ -64,12 +64,13 @@ class avmp_config_t(C.Structure):
                 ("n_q_heads", C.c_uint32), ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
                 ("ssm_heads", C.c_uint32), ("ssm_headdim", C.c_uint32), ("ssm_dstate", C.c_uint32),
                 ("ssm_state_dtype", C.c_uint32), ("ssm_conv_kernel", C.c_uint32),
-                ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
+                ("ssm_pad_to_kv_page", C.c_uint32), ("kv_capacity", C.c_uint32), ("ssm_capacity", C.c_uint32),
                 ("max_vid", C.c_uint32 * 2), ("slot_rank", C.POINTER(C.c_uint32) * 2)]
 
 
 class avmp_geometry_t(C.Structure):
-    _fields_ = [("unit_bytes", C.c_uint64 * 2), ("usable_bytes", C.c_uint64),
+    _fields_ = [("unit_bytes", C.c_uint64 * 2), ("ssm_native_bytes", C.c_uint64),
+                ("usable_bytes", C.c_uint64),
                 ("max_slots", C.c_uint32 * 2)]
 
 
@@ -185,7 +186,7 @@ def make_config(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, ssm_
                 ssm_headdim: int, ssm_dstate: int, kv_capacity: int, ssm_capacity: int,
                 slot_rank: Optional[Sequence[Optional[np.ndarray]]] = None,
                 max_vid: Sequence[int] = (0, 0), page_tokens: int = 16, state_dtype: str = "f32",
-                conv_kernel: int = 0):
+                conv_kernel: int = 0, pad_ssm_to_kv_page: bool = False):
     """Returns (avmp_config_t, keepalive): keepalive holds the rank arrays the struct points to."""
     cfg = avmp_config_t()
     cfg.dtype = AVMP_F32 if dtype == "f32" else AVMP_BF16
@@ -194,6 +195,7 @@ def make_config(dtype: str, n_q_heads: int, n_kv_heads: int, head_dim: int, ssm_
     cfg.ssm_heads, cfg.ssm_headdim, cfg.ssm_dstate = ssm_heads, ssm_headdim, ssm_dstate
     cfg.ssm_state_dtype = AVMP_F32 if state_dtype == "f32" else AVMP_BF16
     cfg.ssm_conv_kernel = conv_kernel
+    cfg.ssm_pad_to_kv_page = 1 if pad_ssm_to_kv_page else 0
     cfg.kv_capacity, cfg.ssm_capacity = kv_capacity, ssm_capacity
     cfg.max_vid[0], cfg.max_vid[1] = max_vid
     keep = []

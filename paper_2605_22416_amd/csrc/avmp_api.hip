@@ -216,6 +216,8 @@ bool shape_from_config(const avmp_config_t* c, avmp::ShapeArgs* s) {
       !avmp::conv_supported(c->dtype, c->ssm_conv_kernel, c->ssm_heads, c->ssm_headdim, n))
     return false;
   s->conv_kernel = c->ssm_conv_kernel;
+  if (c->ssm_pad_to_kv_page > 1) return false;
+  s->pad_ssm_to_kv_page = c->ssm_pad_to_kv_page == 1;
   s->page_tokens = c->attention_page_tokens;
   s->n_q_heads = c->n_q_heads;
   s->n_kv_heads = c->n_kv_heads;
@@ -508,6 +510,7 @@ int avmp_geometry(const avmp_config_t* cfg, size_t arena_bytes, avmp_geometry_t*
     return fail(AVMP_ERR_INVALID_ARG, "unsupported shape or arena size");
   out->unit_bytes[0] = g.unit[0];
   out->unit_bytes[1] = g.unit[1];
+  out->ssm_native_bytes = g.ssm_native;
   out->usable_bytes = g.usable;
   out->max_slots[0] = g.max_slots[0];
   out->max_slots[1] = g.max_slots[1];

@@ -32,6 +32,7 @@ __global__ __launch_bounds__(256) void zero_units_kernel(DevPools P, int pool,
   uint4* dst = reinterpret_cast<uint4*>(P.arena + off);
   const uint64_t n16 = P.unit[pool] / 16;
   const uint4 z = make_uint4(0, 0, 0, 0);
+  // plain stores: with the non-temporal hint this fill measured 24.5 us against 22.4 us
   for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += uint64_t(gridDim.x) * 256)
     dst[i] = z;
 }

@@ -91,7 +91,9 @@ bool compute_geometry(const ShapeArgs& s, uint64_t arena_bytes, Geometry* g) {
   if (s.conv_kernel)   // + the inputs of the last K-1 tokens on the x, B and C channels
     block += uint64_t(s.conv_kernel - 1) *
              (uint64_t(s.ssm_heads) * s.ssm_headdim + 2ull * s.ssm_dstate) * s.elem_bytes;
-  g->unit[1] = round_up(block, 16);
+  g->ssm_native = round_up(block, 16);
+  // a unified pool hands out one page size: the block takes a whole number of KV pages
+  g->unit[1] = s.pad_ssm_to_kv_page ? round_up(g->ssm_native, g->unit[0]) : g->ssm_native;
   g->usable = arena_bytes / 128 * 128;
   for (int p = 0; p < kPools; ++p) {
     uint64_t m = g->usable / g->unit[p];

@@ -43,6 +43,7 @@ struct Move {              // one unit copy of a migration
 };
 
 struct Geometry {
+  uint64_t ssm_native;           // SSM block bytes before unified-pool padding (= unit[1] without it)
   uint64_t unit[kPools];
   uint64_t usable;
   uint32_t max_slots[kPools];
@@ -57,6 +58,7 @@ struct ShapeArgs {
   uint32_t elem_bytes, page_tokens, n_q_heads, n_kv_heads, head_dim, ssm_heads, ssm_headdim,
       ssm_dstate, state_bytes;
   uint32_t conv_kernel = 0;   // taps of the short convolution; 0 = no window in the SSM block
+  bool pad_ssm_to_kv_page = false;   // unified-pool sizing: the block padded to whole KV pages
 };
 
 // Returns false if the shape is unusable (zero sizes, more than 2^30 slots).

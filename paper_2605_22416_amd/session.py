@@ -93,7 +93,8 @@ class DeviceSession:
         cfg, self._keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                                          spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate,
                                          sc.kv_capacity, sc.ssm_capacity, slot_rank=sc.slot_rank,
-                                         state_dtype=spec.state_dtype, conv_kernel=spec.conv_kernel)
+                                         state_dtype=spec.state_dtype, conv_kernel=spec.conv_kernel,
+                                         pad_ssm_to_kv_page=spec.pad_ssm_to_kv_page)
         rc, self.p = av.avmp_pools_create(cfg, self.base, sc.arena_bytes)
         if rc != av.AVMP_OK:
             raise RuntimeError("avmp_pools_create: " + av.avmp_last_error())

@@ -8,7 +8,7 @@ from gen import inputs
 def oracle_shape(spec):
     return orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                      spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype,
-                     spec.conv_kernel)
+                     spec.conv_kernel, spec.pad_ssm_to_kv_page)
 
 
 def alloc_order(sc):

@@ -710,6 +710,34 @@ def test_short_convolution_in_front_of_the_recurrence(dtype, state_dtype, K, H, 
     g.close()
 
 
+def test_blocks_padded_to_whole_pages_unified_pool_sizing():
+    """The unified-pool sizing mode on the device: blocks sit a padded unit apart, the
+    state (and the window) at the front of each; two steps with a migration between."""
+    from paper_2605_22416_amd import binding as av
+    spec = inputs.with_padded_blocks(inputs.with_conv(inputs.ModelSpec(
+        "padded", "bf16", 16, 8, 2, 64, 8, 16, 32, (inputs.SSM, inputs.ATTN, inputs.SSM), True), 3))
+    assert spec.ssm_native_bytes == 17152 and spec.ssm_block_bytes == 3 * spec.kv_page_bytes == 24576
+    ctx = [5, 130, 48, 0]
+    sc = inputs.make_scenario(spec, "uniform_short", len(ctx), seed=91, ctx=ctx, headroom=2.0)
+    op, g, kv, ssm = _both(sc, poison=True)
+    conv = inputs.conv_weights(spec, seed=91)
+    for step in range(2):
+        if step == 1:
+            ores = op.migrate(1, 2)
+            rc, res = av.avmp_migrate(g.p, 1, 2)
+            assert rc == ores.code == orc.OK
+            assert (res.units_copied, res.recipient_gain, res.bytes_wasted) == \
+                (ores.units_copied, ores.recipient_gain, ores.bytes_wasted) and res.recipient_gain == 6
+            _check_translation(g, op, list(kv.reshape(-1)) + list(ssm.reshape(-1)))
+        inp = inputs.step_inputs(spec, len(ctx), seed=91, step=step)
+        ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, inp["x"], inp["dt"],
+                                      inp["A"], inp["B"], inp["C"], xbc=inp["xbc"], conv_w=conv[0], conv_b=conv[1])
+        o, y = g.step(inp, conv=conv)
+        _check_outputs(spec, o, y, ref_o, ref_y, "padded blocks step %d" % step)
+    _check_states(spec, g, op, ssm, "padded blocks")
+    g.close()
+
+
 def test_convolution_inputs_are_required_and_checked():
     from paper_2605_22416_amd import binding as av
     spec = inputs.with_conv(inputs.TINY, 4)

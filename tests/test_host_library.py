@@ -29,7 +29,7 @@ def _lib_pools(spec, arena_bytes, kv_cap, ssm_cap, ranks):
     cfg, keep = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
                                spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, kv_cap, ssm_cap,
                                slot_rank=ranks, state_dtype=spec.state_dtype,
-                               conv_kernel=spec.conv_kernel)
+                               conv_kernel=spec.conv_kernel, pad_ssm_to_kv_page=spec.pad_ssm_to_kv_page)
     rc, p = av.avmp_pools_create(cfg, None, arena_bytes)
     assert rc == av.AVMP_OK, av.avmp_last_error()
     return p
@@ -67,6 +67,27 @@ def test_geometry_with_a_convolution_window():
     assert av.avmp_geometry(cfg, 1 << 30)[0] == av.AVMP_OK
 
 
+def test_padded_unified_geometry_reports_native_and_padded_sizes():
+    """The unified-pool sizing mode against the hand-evaluated sizes, and what it costs."""
+    import os
+    specs = {"tiny_fp32": inputs.TINY, "jamba_mini_like": inputs.JAMBA_MINI}
+    rows = [ln.split() for ln in open(os.path.join(os.path.dirname(__file__), "golden", "padded_unified_sizes.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    for name, state_dtype, k, page, native, padded in rows:
+        spec = specs[name]
+        for pad in (False, True):
+            cfg, _ = av.make_config(spec.dtype, spec.n_q_heads, spec.n_kv_heads, spec.head_dim, spec.ssm_heads,
+                                    spec.ssm_headdim, spec.ssm_dstate, 1, 1, state_dtype=state_dtype,
+                                    conv_kernel=int(k), pad_ssm_to_kv_page=pad)
+            rc, g = av.avmp_geometry(cfg, 1 << 30)
+            assert rc == av.AVMP_OK
+            assert (g.unit_bytes[0], g.ssm_native_bytes) == (int(page), int(native))
+            assert g.unit_bytes[1] == (int(padded) if pad else int(native))
+            assert g.max_slots[1] == (1 << 30) // g.unit_bytes[1]
+    cfg.ssm_pad_to_kv_page = 2
+    assert av.avmp_geometry(cfg, 1 << 30)[0] == av.AVMP_ERR_INVALID_ARG
+
+
 def test_create_rejects_bad_configs():
     spec = inputs.TINY
     ok = dict(dtype="f32", n_q_heads=4, n_kv_heads=2, head_dim=64, ssm_heads=4, ssm_headdim=32,
@@ -93,10 +114,14 @@ def _check_same(op, lp):
     assert av.avmp_stats(lp) == op.stats()
 
 
-@pytest.mark.parametrize("seed,conv,n_ops", [(1, 0, 50000), (2, 0, 40000), (3, 3, 12000)])
-def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops):
-    # with a 3-tap convolution window the block is 9472 bytes: units that divide nothing evenly
+@pytest.mark.parametrize("seed,conv,n_ops,pad", [(1, 0, 50000, False), (2, 0, 40000, False), (3, 3, 12000, False),
+                                                  (4, 3, 12000, True)])
+def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops, pad):
+    # with a 3-tap convolution window the block is 9472 bytes: units that divide nothing evenly;
+    # padded to whole pages it becomes 16384 bytes
     spec = inputs.with_conv(inputs.TINY, conv) if conv else inputs.TINY
+    if pad:
+        spec = inputs.with_padded_blocks(spec)
     rng = np.random.default_rng(seed)
     kv_cap, ssm_cap = 37, 11
     arena = kv_cap * spec.kv_page_bytes + ssm_cap * spec.ssm_block_bytes + 128 * 5
@@ -158,7 +183,7 @@ def test_random_traces_match_the_oracle_bit_for_bit(seed, conv, n_ops):
                 rc, pl, sl, off = av.avmp_resolve(lp, h)
                 assert rc == av.AVMP_OK and (pl, sl, off) == op.resolve(h)
     _check_same(op, lp)
-    assert n_cap > 100 and n_mig > 100 and n_bad > 50 and n_gap > 5
+    assert n_cap > 100 and n_mig > 100 and n_bad > 50 and (n_gap > 5 or pad)   # equal units leave no whole unit in the gap
     assert av.avmp_resolve(lp, 0xFFFFFFFF)[0] == av.AVMP_ERR_INVALID_HANDLE
     av.avmp_pools_destroy(lp)
 

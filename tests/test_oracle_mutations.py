@@ -74,6 +74,8 @@ MUTATIONS = [
     ("conv window stores the token in the oldest row", "            rows[-1] = u_raw[r].view(np.uint8)", "            rows[0] = u_raw[r].view(np.uint8)"),
     ("conv hands out C as B", "        return x, out[:, H * P: H * P + N], out[:, H * P + N:]", "        return x, out[:, H * P + N:], out[:, H * P: H * P + N]"),
     ("block size ignores the conv window", "                raw += (self.conv_kernel - 1) * self.conv_dim * self.elem_bytes", "                raw += 0"),
+    ("padding rounds down", "            unit = round_up(unit, self.unit_bytes(POOL_KV))", "            unit = max(unit // self.unit_bytes(POOL_KV), 1) * self.unit_bytes(POOL_KV)"),
+    ("padding ignored", "        if pool == POOL_SSM and self.pad_ssm_to_kv_page:", "        if False:"),
     ("decode step skips the convolution", "            elif self.shape.conv_kernel:", "            elif False:"),
 ]
 

@@ -24,7 +24,8 @@ def _rows(name):
 
 def _shape(spec):
     return orc.Shape(spec.dtype, spec.page_tokens, spec.n_q_heads, spec.n_kv_heads, spec.head_dim,
-                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate)
+                     spec.ssm_heads, spec.ssm_headdim, spec.ssm_dstate, spec.state_dtype,
+                     spec.conv_kernel, spec.pad_ssm_to_kv_page)
 
 
 TINY = _shape(inputs.TINY)
@@ -92,6 +93,29 @@ def test_unit_sizes_closed_form():
         assert sh.unit_bytes(orc.POOL_SSM) == int(r[9])
         # the input generator's own size arithmetic agrees with the fixture too
         assert spec.kv_page_bytes == int(r[8]) and spec.ssm_block_bytes == int(r[9])
+
+
+def test_padded_unified_sizes_closed_form():
+    """The unified-pool sizing mode: the block grows to whole attention pages, nothing else."""
+    specs = {"tiny_fp32": inputs.TINY, "jamba_mini_like": inputs.JAMBA_MINI}
+    for name, state_dtype, k, page, native, padded in _rows("padded_unified_sizes.txt"):
+        spec = specs[name]
+        if state_dtype != "f32":
+            spec = inputs.with_state_dtype(spec, state_dtype)
+        if int(k):
+            spec = inputs.with_conv(spec, int(k))
+        plain, pad = _shape(spec), _shape(inputs.with_padded_blocks(spec))
+        assert plain.unit_bytes(orc.POOL_KV) == pad.unit_bytes(orc.POOL_KV) == int(page)
+        assert plain.unit_bytes(orc.POOL_SSM) == pad.native_ssm_bytes() == int(native)
+        assert pad.unit_bytes(orc.POOL_SSM) == int(padded) and int(padded) % int(page) == 0
+        # the generator's size arithmetic agrees
+        assert inputs.with_padded_blocks(spec).ssm_block_bytes == int(padded)
+        assert inputs.with_padded_blocks(spec).ssm_native_bytes == int(native)
+    # with padding a budget holds fewer blocks: same arena, capacities by the padded unit
+    sh = _shape(inputs.with_padded_blocks(inputs.TINY))
+    p = orc.Pools(sh, 4 * 16384 + 4 * 16384, 4, 4, with_data=False)
+    assert p.unit[1] == 16384 and p.gap == 0
+    assert p.migrate(0, 1).recipient_gain == 1          # a page buys one padded block, not two
 
 
 def test_alignment_rules():
