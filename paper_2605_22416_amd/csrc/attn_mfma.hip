@@ -232,91 +232,83 @@ __device__ __forceinline__ size_t partial_slot(uint32_t g, uint32_t runs, uint32
 }
 
 // Combines the np partial results of (request r, KV head g), left by runs wa .. wa + np - 1,
-// into the group's output rows.  One wavefront; the order of every sum depends on np alone.
+// into the output rows of HS query heads of the group, head0 .. head0 + HS - 1.  One
+// wavefront; the order of every sum depends on np alone.
 //   statistics: lane (piece kk, head i) of a block of 64 / HS pieces holds that piece's running
 //     max and sum; the row maximum M_i and the total L_i come from shuffles across the block;
 //   rows: a partial row is D floats = D / 4 lanes of float4, so one load instruction fetches
 //     64 / (D / 4) rows; lane group `sub` takes the pieces k = sub (mod that many), adds them
 //     up in ascending k, and the groups are added in ascending order at the end.
-// HS = head stride of the statistics layout (4 for query groups up to 4, else 16).
+// Row loads go out in chunks of up to 32 per lane, and in the usual case of a single block of
+// statistics the first chunk is issued before anything is waited for.
 template <int D, int HS>
 __device__ void merge_pieces(const AttnLaunch& a, uint32_t g, uint32_t r, uint32_t wa, uint32_t np,
-                             uint32_t lane) {
+                             uint32_t lane, uint32_t head0) {
   constexpr uint32_t LPR = D / 4;            // lanes per partial row
   constexpr uint32_t RPL = 64 / LPR;         // rows per load instruction: 4, 2 or 1
   constexpr uint32_t PB = 64 / HS;           // pieces per block of statistics
+  constexpr uint32_t ROUNDS = PB / RPL;      // load rounds that cover a block
+  constexpr uint32_t CH = ROUNDS * HS <= 32 ? ROUNDS : 32 / HS;     // rounds per chunk of loads
   const uint32_t Hq = a.n_q_heads, Gq = Hq / a.n_kv_heads;
-  const uint32_t kk = lane / HS, hi = lane % HS;       // statistics role
-  const uint32_t sub = lane / LPR, c = lane % LPR;     // row role
-  auto row_of = [&](uint32_t k, uint32_t i) -> size_t {
-    return partial_slot(g, a.runs, wa + k, k == 0) * Gq + i;
+  const uint32_t kk = lane / HS, hi = head0 + lane % HS;     // statistics role
+  const uint32_t sub = lane / LPR, c = lane % LPR;           // row role
+  auto row_of = [&](uint32_t k, uint32_t head) -> size_t {
+    return partial_slot(g, a.runs, wa + k, k == 0) * Gq + head;
   };
   float M = -INFINITY;                        // row maximum of head hi over all pieces
   float L = 0.f;                              // this lane's share of the total of head hi
   float4 acc[HS];
 #pragma unroll
   for (int i = 0; i < HS; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (np <= PB) {
-    // the usual case, one block of statistics: every load is issued before anything is used
+  const bool one_block = np <= PB;
+  if (!one_block) {                           // the maxima need a pass of their own
+    for (uint32_t base = 0; base < np; base += 4 * PB) {
+      float m4[4];
+#pragma unroll
+      for (uint32_t u = 0; u < 4; ++u) {
+        const uint32_t k = base + u * PB + kk;
+        m4[u] = (k < np && hi < Gq) ? a.part_ml[row_of(k, hi) * 2] : -INFINITY;
+      }
+      M = fmaxf(fmaxf(M, fmaxf(m4[0], m4[1])), fmaxf(m4[2], m4[3]));
+    }
+#pragma unroll
+    for (uint32_t o = HS; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, int(o)));
+  }
+  for (uint32_t base = 0; base < np; base += PB) {
     float2 ml = make_float2(-INFINITY, 0.f);
-    if (kk < np && hi < Gq) ml = *reinterpret_cast<const float2*>(a.part_ml + row_of(kk, hi) * 2);
-    float4 v[PB / RPL][HS];
+    if (base + kk < np && hi < Gq) ml = *reinterpret_cast<const float2*>(a.part_ml + row_of(base + kk, hi) * 2);
+    const uint32_t rounds = (min(np - base, PB) + RPL - 1) / RPL;
+    float wgt = 0.f;
+    for (uint32_t t0 = 0; t0 < rounds; t0 += CH) {
+      float4 v[CH][HS];
 #pragma unroll
-    for (uint32_t t = 0; t < PB / RPL; ++t) {
-      const uint32_t k = t * RPL + sub;
+      for (uint32_t t = 0; t < CH; ++t) {
+        const uint32_t k = base + (t0 + t) * RPL + sub;
 #pragma unroll
-      for (int i = 0; i < HS; ++i)
-        v[t][i] = (k < np && uint32_t(i) < Gq)
-                      ? *reinterpret_cast<const float4*>(a.part_o + row_of(k, i) * D + 4 * c)
-                      : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    M = ml.x;
-#pragma unroll
-    for (uint32_t o = HS; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, int(o)));
-    const float wgt = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);   // -inf: a piece whose pages were all skipped
-    L = ml.y * wgt;
-#pragma unroll
-    for (uint32_t t = 0; t < PB / RPL; ++t) {
-      const uint32_t k2 = t * RPL + sub;
-#pragma unroll
-      for (int i = 0; i < HS; ++i) {
-        const float w = __shfl(wgt, int(k2 * HS + i));            // 0 where the piece does not exist
-        acc[i].x += w * v[t][i].x;
-        acc[i].y += w * v[t][i].y;
-        acc[i].z += w * v[t][i].z;
-        acc[i].w += w * v[t][i].w;
+        for (int i = 0; i < HS; ++i)
+          v[t][i] = (t0 + t < rounds && k < np && head0 + i < Gq)
+                        ? *reinterpret_cast<const float4*>(a.part_o + row_of(k, head0 + i) * D + 4 * c)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
       }
-    }
-  } else {
-    for (uint32_t base = 0; base < np; base += PB) {
-      const uint32_t k = base + kk;
-      if (k < np && hi < Gq) M = fmaxf(M, a.part_ml[row_of(k, hi) * 2]);
-    }
+      if (t0 == 0) {                          // the block's weights, once its statistics are in
+        if (one_block) {
+          M = ml.x;
 #pragma unroll
-    for (uint32_t o = HS; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, int(o)));
-    for (uint32_t base = 0; base < np; base += PB) {
-      float wgt = 0.f;
-      {
-        const uint32_t k = base + kk;
-        if (k < np && hi < Gq) {
-          const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + row_of(k, hi) * 2);
-          wgt = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);
-          L += ml.y * wgt;
+          for (uint32_t o = HS; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, int(o)));
         }
+        wgt = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);     // -inf: a piece whose pages were all skipped
+        L += ml.y * wgt;
       }
 #pragma unroll
-      for (uint32_t t = 0; t < PB / RPL; ++t) {
-        const uint32_t k2 = t * RPL + sub, k = base + k2;    // this lane group's piece of the round
+      for (uint32_t t = 0; t < CH; ++t) {
+        const uint32_t k2 = (t0 + t) * RPL + sub;            // piece within the block
 #pragma unroll
         for (int i = 0; i < HS; ++i) {
-          const float w = __shfl(wgt, int(k2 * HS + i));
-          if (k < np && uint32_t(i) < Gq) {
-            const float4 v = *reinterpret_cast<const float4*>(a.part_o + row_of(k, i) * D + 4 * c);
-            acc[i].x += w * v.x;
-            acc[i].y += w * v.y;
-            acc[i].z += w * v.z;
-            acc[i].w += w * v.w;
-          }
+          const float w = __shfl(wgt, int((k2 % PB) * HS + i));   // 0 where the piece does not exist
+          acc[i].x += w * v[t][i].x;
+          acc[i].y += w * v[t][i].y;
+          acc[i].z += w * v[t][i].z;
+          acc[i].w += w * v[t][i].w;
         }
       }
     }
@@ -335,9 +327,9 @@ __device__ void merge_pieces(const AttnLaunch& a, uint32_t g, uint32_t r, uint32
       sum.z += __shfl(acc[i].z, src);
       sum.w += __shfl(acc[i].w, src);
     }
-    const float Li = __shfl(L, i);            // lane i (piece 0 of the block, head i) holds the total
-    if (sub == 0 && uint32_t(i) < Gq) {
-      float* orow = a.o + (size_t(r) * Hq + size_t(g) * Gq + i) * D;
+    const float Li = __shfl(L, i);            // lane i (piece 0 of the block, head head0 + i) holds the total
+    if (sub == 0 && head0 + i < Gq) {
+      float* orow = a.o + (size_t(r) * Hq + size_t(g) * Gq + head0 + i) * D;
       const float inv = Li > 0.f ? 1.f / Li : 0.f;
       *reinterpret_cast<float4*>(orow + 4 * c) =
           Li > 0.f ? make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv)
@@ -545,20 +537,27 @@ void attn_mfma_kernel(AttnLaunch a) {
   }
 }
 
-// Merge of the partial results that the runs left: one wavefront per (KV head, request),
-// which handles the whole query group.  The runs that hold the request's first and last
-// page follow from its position on the plan's cost axis.
+// Merge of the partial results that the runs left, one workgroup of four wavefronts per
+// (KV head, request).  A query group of up to four heads whose request was cut into at most 16
+// pieces (every request of an ordinary batch) is one wavefront's work, all heads at once; a
+// longer list of pieces, or a wider group, is taken head by head, the heads shared out over
+// the four wavefronts.  The runs that hold the request's first and last page follow from its
+// position on the plan's cost axis.
 template <int D>
-__global__ __launch_bounds__(64) void attn_merge_runs_kernel(AttnLaunch a) {
-  const uint32_t g = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_merge_runs_kernel(AttnLaunch a) {
+  const uint32_t g = blockIdx.x, r = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t start = a.prefix[r], end = a.prefix[r + 1];
   if (start == end) return;                 // no resident tokens: the plan wrote the zero rows
   const uint64_t cpw = a.plan[1];
   const uint64_t at = uint64_t(start) + uint64_t(kRequestCost) * r + kRequestCost;
   const uint32_t wa = uint32_t(at / cpw), wb = uint32_t((at + (end - start) - 1) / cpw);
   if (wa == wb) return;                     // one run covered it and wrote the rows
-  if (a.n_q_heads / a.n_kv_heads <= 4) merge_pieces<D, 4>(a, g, r, wa, wb - wa + 1, lane);
-  else merge_pieces<D, 16>(a, g, r, wa, wb - wa + 1, lane);
+  const uint32_t np = wb - wa + 1, Gq = a.n_q_heads / a.n_kv_heads;
+  if (Gq <= 4 && np <= 16) {
+    if (wave == 0) merge_pieces<D, 4>(a, g, r, wa, np, lane, 0);
+    return;
+  }
+  for (uint32_t head = wave; head < Gq; head += 4) merge_pieces<D, 1>(a, g, r, wa, np, lane, head);
 }
 
 }  // namespace
@@ -614,9 +613,9 @@ hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s) {
 hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s) {
   const dim3 grid(a.n_kv_heads, a.batch);
   switch (a.head_dim) {
-    case 64: attn_merge_runs_kernel<64><<<grid, dim3(64), 0, s>>>(a); break;
-    case 128: attn_merge_runs_kernel<128><<<grid, dim3(64), 0, s>>>(a); break;
-    default: attn_merge_runs_kernel<256><<<grid, dim3(64), 0, s>>>(a); break;
+    case 64: attn_merge_runs_kernel<64><<<grid, dim3(256), 0, s>>>(a); break;
+    case 128: attn_merge_runs_kernel<128><<<grid, dim3(256), 0, s>>>(a); break;
+    default: attn_merge_runs_kernel<256><<<grid, dim3(256), 0, s>>>(a); break;
   }
   return hipGetLastError();
 }
