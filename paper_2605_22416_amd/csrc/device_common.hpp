@@ -30,10 +30,11 @@ constexpr uint32_t kDevUnmapped = 0xFFFFFFFFu;
 // produce an address outside the arena.
 __device__ __forceinline__ uint64_t translate_offset(const DevPools& P, uint32_t h,
                                                      uint32_t want_pool) {
+  const uint32_t cap = P.capacity[want_pool];            // does not depend on the handle: goes out first
   const uint32_t pool = h >> 30, vid = h & 0x3FFFFFFFu;
   if (pool != want_pool || vid >= P.max_vid[want_pool]) return ~0ull;
   const uint32_t slot = P.table[P.vid_base[want_pool] + vid];
-  if (slot >= P.capacity[want_pool]) return ~0ull;       // also catches 0xFFFFFFFF
+  if (slot >= cap) return ~0ull;                         // also catches 0xFFFFFFFF
   return want_pool == 0 ? uint64_t(slot) * P.unit[0]
                         : P.usable - (uint64_t(slot) + 1) * P.unit[1];
 }

@@ -64,21 +64,24 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
   const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
   const uint32_t H = a.heads, Pd = a.headdim;
   const uint32_t N = NS ? uint32_t(NS) : a.dstate;
-  const uint64_t off = translate_offset(a.P, a.handles[r], 1);
+  const uint32_t lpr = N / 4;                  // lanes per row (power of two, <= 64)
+  const uint32_t col = tid & (lpr - 1);
+  const uint32_t row0 = tid / lpr;
+  const uint32_t rpi = THREADS / lpr;          // rows per pass of the workgroup
+  // the step's own inputs are requested before the handle -> table -> block chain is waited for
+  const uint32_t handle = a.handles[r];
+  const float dt = a.dt[size_t(r) * H + h];
+  const float Ah = a.A[h];
+  const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
+  const float4 Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
+  const uint64_t off = translate_offset(a.P, handle, 1);
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
   if (off == ~0ull) {
     if (tid == 0) count_fault(a.P);
     for (uint32_t p = tid; p < Pd; p += THREADS) yrow[p] = 0.f;
     return;
   }
-  const uint32_t lpr = N / 4;                  // lanes per row (power of two, <= 64)
-  const uint32_t col = tid & (lpr - 1);
-  const uint32_t row0 = tid / lpr;
-  const uint32_t rpi = THREADS / lpr;          // rows per pass of the workgroup
-  const float dt = a.dt[size_t(r) * H + h];
-  const float decay = expf(dt * a.A[h]);
-  const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
-  const float4 Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
+  const float decay = expf(dt * Ah);
   const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
   float* tile = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N;
   const __amdgpu_buffer_rsrc_t rsrc = tile_descriptor(tile, Pd * N * 4);
