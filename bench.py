@@ -701,7 +701,11 @@ def main():
     sweep_capacity = None
     if args.workload == "uniform_short" and not args.no_capacity_sweep and args.backing == "plain":
         torch.cuda.empty_cache()
-        sweep_capacity = capacity_migration_sweep(inputs.JAMBA_MINI, stream)
+        try:
+            sweep_capacity = capacity_migration_sweep(inputs.JAMBA_MINI, stream)
+        except (AssertionError, RuntimeError, MemoryError) as e:
+            # an extra leg: the headline line is printed whatever happens to it
+            sweep_capacity = {"failed": "%s: %s" % (type(e).__name__, e)}
 
     out = {
         "metric": "hybrid_decode_step_achieved_hbm_GBps_batch%d" % sc.batch,

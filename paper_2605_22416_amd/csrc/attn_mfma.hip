@@ -114,28 +114,34 @@ struct PrepareArgs {
   uint4* desc;                // [runs] out
   float* o;                   // [n_attn][batch][n_q_heads * head_dim]: rows of empty requests
   uint32_t batch, max_pages, runs, append, n_attn, row_floats;
+  uint32_t pitch_log2, page_tiles;   // translation blocks: see attn_prepare_kernel
 };
 
 __device__ void plan_block(const PrepareArgs& a) {
-  __shared__ uint32_t sums[1024];
+  __shared__ uint32_t sums[1024];      // inclusive page sums at the end of each thread's segment
+  __shared__ uint32_t wave_sums[16];
   const uint32_t tid = threadIdx.x, batch = a.batch, runs = a.runs;
   const uint32_t seg = (batch + 1023) / 1024;
   const uint32_t lo = min(batch, tid * seg), hi = min(batch, lo + seg);
   uint32_t local = 0;
   for (uint32_t r = lo; r < hi; ++r) local += pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
-  sums[tid] = local;
-  __syncthreads();
-  for (uint32_t off = 1; off < 1024; off <<= 1) {          // inclusive scan
-    const uint32_t add = tid >= off ? sums[tid - off] : 0;
-    __syncthreads();
-    sums[tid] += add;
-    __syncthreads();
+  // inclusive scan over the 1024 threads: inside each wavefront, then over the 16 wavefronts
+  uint32_t incl = local;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = __shfl_up(incl, off);
+    if ((tid & 63u) >= uint32_t(off)) incl += up;
   }
-  uint32_t run = sums[tid] - local;                         // exclusive start of this segment
+  if ((tid & 63u) == 63u) wave_sums[tid >> 6] = incl;
+  __syncthreads();
+  for (uint32_t wv = 0; wv < (tid >> 6); ++wv) incl += wave_sums[wv];
+  sums[tid] = incl;
+  uint32_t run = incl - local;                              // exclusive start of this segment
   for (uint32_t r = lo; r < hi; ++r) {
     a.prefix[r] = run;
     run += pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
   }
+  __syncthreads();                                          // sums[] and prefix[] visible to the block
   const uint32_t total = sums[1023];
   const uint64_t total_cost = uint64_t(total) + uint64_t(kRequestCost) * batch;
   // equal shares, but room for at least kMinRunPages pages: with few pages in the batch,
@@ -146,7 +152,12 @@ __device__ void plan_block(const PrepareArgs& a) {
     a.plan[0] = total;
     a.plan[1] = uint32_t(cpw);
   }
-  __syncthreads();                                          // prefix[] visible to the block
+  // pages before request r: up to 1024 requests every thread's segment is one request and the
+  // sums in shared memory answer; beyond that the array just written does
+  auto pages_before = [&](uint32_t r) -> uint32_t {
+    if (seg == 1) return r == 0 ? 0u : sums[r - 1];
+    return a.prefix[r];
+  };
   // first page at or after cost position c: (request, page in it, index in the page sequence)
   auto first_page_at = [&](uint64_t c, uint32_t* rq, uint32_t* pg) -> uint32_t {
     if (c >= total_cost) {
@@ -158,13 +169,14 @@ __device__ void plan_block(const PrepareArgs& a) {
     uint32_t lo_r = 0, hi_r = batch;
     while (hi_r - lo_r > 1) {
       const uint32_t mid = (lo_r + hi_r) / 2;
-      if (uint64_t(a.prefix[mid]) + uint64_t(kRequestCost) * mid <= c) lo_r = mid; else hi_r = mid;
+      if (uint64_t(pages_before(mid)) + uint64_t(kRequestCost) * mid <= c) lo_r = mid; else hi_r = mid;
     }
-    const uint64_t at = uint64_t(a.prefix[lo_r]) + uint64_t(kRequestCost) * lo_r + kRequestCost;   // its page 0
+    const uint32_t before = pages_before(lo_r);
+    const uint64_t at = uint64_t(before) + uint64_t(kRequestCost) * lo_r + kRequestCost;   // its page 0
     const uint32_t p = c > at ? uint32_t(c - at) : 0;       // c < position of request lo_r + 1, so p < its pages
     *rq = lo_r;                                             // (or p = 0 in a request without pages: the
     *pg = p;                                                //  walk skips it)
-    return a.prefix[lo_r] + p;
+    return before + p;
   };
   for (uint32_t w = tid; w < runs; w += 1024) {
     uint32_t r0, p0, r1, p1;
@@ -209,20 +221,26 @@ __global__ __launch_bounds__(1024) void attn_prepare_kernel(PrepareArgs a) {
     plan_block(a);
     return;
   }
-  // four entries per thread; a row's entries beyond the request's pages are left as they are
-  const uint64_t per_layer = uint64_t(a.batch) * a.max_pages;
-  const uint64_t entries = per_layer * a.n_attn;
-  for (uint32_t k = 0; k < 4; ++k) {
-    const uint64_t e = (uint64_t(blockIdx.x - 1) * 4 + k) * 1024 + threadIdx.x;
-    if (e >= entries) return;
-    const uint32_t r = uint32_t((e % per_layer) / a.max_pages), page = uint32_t(e % a.max_pages);
-    if (page >= pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages)) continue;
-    const uint64_t off = translate_offset(a.P, a.handles[e], 0);
-    uint32_t slot = kDevUnmapped;
-    if (off == ~0ull) count_fault(a.P);
-    else slot = uint32_t(off / a.P.unit[0]);
-    a.slots[e] = slot;
-  }
+  // One entry per thread.  Rows of up to 1024 pages: a block takes 1024 >> pitch_log2 whole
+  // rows, each on a power-of-two pitch; longer rows: page_tiles blocks of 1024 entries per
+  // row.  Entries beyond the request's pages are left as they are.
+  const uint32_t tile = blockIdx.x - 1;
+  const uint32_t row_group = tile / a.page_tiles, page_tile = tile % a.page_tiles;
+  const uint32_t row = (row_group << (10 - a.pitch_log2)) + (threadIdx.x >> a.pitch_log2);
+  const uint32_t page = page_tile * 1024 + (threadIdx.x & ((1u << a.pitch_log2) - 1u));
+  if (row >= a.n_attn * a.batch || page >= a.max_pages) return;
+  const uint32_t r = row % a.batch;
+  const uint64_t e = uint64_t(row) * a.max_pages + page;
+  // the handle is requested together with the context length, not after it
+  const uint32_t n_ctx = attended_tokens(a.ctx, r, a.append);
+  uint32_t h = a.handles[e];
+  asm volatile("" : "+v"(h));
+  if (page >= pages_of(n_ctx, a.max_pages)) return;
+  const uint64_t off = translate_offset(a.P, h, 0);
+  uint32_t slot = kDevUnmapped;
+  if (off == ~0ull) count_fault(a.P);
+  else slot = uint32_t(off / a.P.unit[0]);
+  a.slots[e] = slot;
 }
 
 // Where run w of KV head g keeps a partial result: a run leaves at most two, slot 1 for
@@ -593,9 +611,14 @@ hipError_t launch_attention_prepare(const AttnLaunch& a, const uint32_t* handles
   p.append = a.append;
   p.n_attn = n_attn;
   p.row_floats = a.n_q_heads * a.head_dim;
-  const uint64_t entries = uint64_t(n_attn) * a.batch * a.max_pages;
-  const uint64_t blocks = 1 + (entries + 4095) / 4096;
-  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  uint32_t pitch_log2 = 0;
+  while (pitch_log2 < 10 && (1u << pitch_log2) < a.max_pages) ++pitch_log2;
+  p.pitch_log2 = pitch_log2;
+  p.page_tiles = a.max_pages > 1024 ? (a.max_pages + 1023) / 1024 : 1;
+  const uint64_t rows = uint64_t(n_attn) * a.batch;
+  const uint32_t rows_per_block = 1024u >> pitch_log2;
+  const uint64_t blocks = 1 + (rows + rows_per_block - 1) / rows_per_block * p.page_tiles;
+  if (rows > 0xFFFFFFFFull || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   attn_prepare_kernel<<<dim3(uint32_t(blocks)), dim3(1024), 0, s>>>(p);
   return hipGetLastError();
 }
