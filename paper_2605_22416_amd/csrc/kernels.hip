@@ -114,7 +114,10 @@ __global__ __launch_bounds__(256) void kv_append_kernel(AttnLaunch a) {
 
 // ---------------------------------------------------------------------------
 // shape-generic paged GQA decode attention: one wavefront per (query head,
-// chunk, request).  Lane = (token t = lane%16, dim quarter = lane/16) for the
+// chunk, request); the wavefronts of up to 16 query heads that share a KV head
+// form one workgroup, so they walk the same pages at the same time on one
+// compute unit and the group's K and V are fetched into its cache once, not once
+// per query head.  Lane = (token t = lane%16, dim quarter = lane/16) for the
 // scores; lane = dim for the weighted sum of V.  Online softmax in the log2
 // domain, fp32 throughout.  Used for fp32 pools and for head shapes the
 // matrix-core kernel does not take.
@@ -128,10 +131,31 @@ __device__ __forceinline__ uint32_t resident_tokens(const AttnLaunch& a, uint32_
   return n > room ? uint32_t(room) : n;
 }
 
+constexpr uint32_t kGenericHeadsPerBlock = 16;
+
+// one 16-byte group of elements as floats
 template <typename E>
-__global__ __launch_bounds__(64) void attn_generic_kernel(AttnLaunch a) {
-  const uint32_t j = blockIdx.x, c = blockIdx.y, r = blockIdx.z;
-  const uint32_t lane = threadIdx.x;
+__device__ __forceinline__ void load_group(const E* p, float* out);
+template <>
+__device__ __forceinline__ void load_group<float>(const float* p, float* out) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <>
+__device__ __forceinline__ void load_group<uint16_t>(const uint16_t* p, float* out) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
+
+template <typename E>
+__global__ __launch_bounds__(64 * kGenericHeadsPerBlock) void attn_generic_kernel(AttnLaunch a) {
+  const uint32_t c = blockIdx.y, r = blockIdx.z;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
   const uint32_t n_tok = resident_tokens(a, r);
   const uint32_t n_pages = (n_tok + 15) / 16;
   const uint32_t nch = chunk_count_for(n_pages);
@@ -140,13 +164,22 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnLaunch a) {
   const uint32_t p0 = c * cp;
   const uint32_t p1 = min(n_pages, p0 + cp);
   const uint32_t D = a.head_dim, G = a.n_kv_heads, Hq = a.n_q_heads;
-  const uint32_t g = j / (Hq / G);
+  // blockIdx.x = (KV head, slice of up to 16 heads of its query group)
+  const uint32_t Gq = Hq / G, slices = (Gq + kGenericHeadsPerBlock - 1) / kGenericHeadsPerBlock;
+  const uint32_t g = blockIdx.x / slices;
+  const uint32_t in_group = (blockIdx.x % slices) * kGenericHeadsPerBlock + wave;
+  const bool has_head = in_group < Gq;
+  const uint32_t j = g * Gq + in_group;
   constexpr uint32_t X = 16 / sizeof(E);
 
-  __shared__ float qs[256];
-  const E* qrow = static_cast<const E*>(a.q) + (size_t(r) * Hq + j) * D;
-  for (uint32_t d = lane; d < D; d += 64) qs[d] = load_elem<E>(qrow + d);
+  __shared__ float q_all[kGenericHeadsPerBlock][256];
+  float* const qs = q_all[wave];
+  if (has_head) {
+    const E* qrow = static_cast<const E*>(a.q) + (size_t(r) * Hq + j) * D;
+    for (uint32_t d = lane; d < D; d += 64) qs[d] = load_elem<E>(qrow + d);
+  }
   __syncthreads();
+  if (!has_head) return;
 
   const float scale_log2 = kLog2e / sqrtf(float(D));
   const uint32_t t = lane & 15, dq = lane >> 4;
@@ -165,8 +198,19 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnLaunch a) {
     const uint32_t n_valid = min(16u, n_tok - page * 16);
     const E* kbase = pg + size_t(g) * D * 16;                       // [D/X][16][X]
     float s = 0.f;
-    for (uint32_t d = dq * DQ; d < (dq + 1) * DQ; ++d)
-      s += qs[d] * load_elem<E>(kbase + ((d / X) * 16 + t) * X + d % X);
+    if (D % (4 * X) == 0) {
+      // a lane's quarter of the dims is whole 16-byte groups: one load per group, and the
+      // 16 token lanes of a group read 256 consecutive bytes
+      for (uint32_t dg = dq * (DQ / X); dg < (dq + 1) * (DQ / X); ++dg) {
+        float kf[X];
+        load_group<E>(kbase + (size_t(dg) * 16 + t) * X, kf);
+#pragma unroll
+        for (uint32_t i = 0; i < X; ++i) s += qs[dg * X + i] * kf[i];
+      }
+    } else {                                    // head_dim is a multiple of X, so of four
+      for (uint32_t d = dq * DQ; d < (dq + 1) * DQ; ++d)
+        s += qs[d] * load_elem<E>(kbase + ((d / X) * 16 + t) * X + d % X);
+    }
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
     s = (t < n_valid) ? s * scale_log2 : -INFINITY;                 // tail slots never count
@@ -180,14 +224,21 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnLaunch a) {
     l = l * alpha + ps;
     m = m_new;
     const E* vbase = pg + size_t(G) * 16 * D + size_t(g) * D * 16;  // [D][16]
+    float pt[16];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] *= alpha;
-    for (uint32_t tt = 0; tt < n_valid; ++tt) {
-      const float pt = __shfl(p, int(tt));
+    for (int tt = 0; tt < 16; ++tt) pt[tt] = __shfl(p, tt);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint32_t d = lane + 64 * i;
-        if (d < D) acc[i] += pt * load_elem<E>(vbase + size_t(d) * 16 + tt);
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t d = lane + 64 * i;
+      if (d < D) {
+        // the 16 tokens of one dim lie side by side; slots beyond the tail hold anything
+        float vf[16];
+#pragma unroll
+        for (uint32_t x = 0; x < 16 / X; ++x) load_group<E>(vbase + size_t(d) * 16 + x * X, vf + x * X);
+        float sum = acc[i] * alpha;
+#pragma unroll
+        for (int tt = 0; tt < 16; ++tt) sum += pt[tt] * (uint32_t(tt) < n_valid ? vf[tt] : 0.f);
+        acc[i] = sum;
       }
     }
   }
@@ -317,11 +368,14 @@ hipError_t launch_kv_append(const AttnLaunch& a, hipStream_t s) {
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
   if (a.plan != nullptr) return launch_attention_mfma(a, s);
-  const dim3 grid(a.n_q_heads, a.max_chunks, a.batch);
+  const uint32_t group = a.n_q_heads / a.n_kv_heads;
+  const uint32_t slices = (group + kGenericHeadsPerBlock - 1) / kGenericHeadsPerBlock;
+  const uint32_t waves = group < kGenericHeadsPerBlock ? group : kGenericHeadsPerBlock;
+  const dim3 grid(a.n_kv_heads * slices, a.max_chunks, a.batch);
   if (a.dtype == 0)
-    attn_generic_kernel<float><<<grid, dim3(64), 0, s>>>(a);
+    attn_generic_kernel<float><<<grid, dim3(64 * waves), 0, s>>>(a);
   else
-    attn_generic_kernel<uint16_t><<<grid, dim3(64), 0, s>>>(a);
+    attn_generic_kernel<uint16_t><<<grid, dim3(64 * waves), 0, s>>>(a);
   return hipGetLastError();
 }
 
