@@ -397,6 +397,9 @@ def main():
     ap.add_argument("--conv-kernel", type=int, default=0, choices=(0, 2, 3, 4),
                     help="taps of the short convolution in front of the recurrence; the SSM blocks "
                          "then also hold its window (0, the headline configuration: none)")
+    ap.add_argument("--pad-ssm-to-kv-page", action="store_true",
+                    help="pad every SSM block to a whole number of KV pages (the unified-pool sizing); "
+                         "with a convolution window the state tiles then keep their 64 KiB alignment")
     ap.add_argument("--graph", action="store_true",
                     help="replay the decode part of the step from a HIP graph captured once (churn "
                          "and migration stay eager; their table updates are flushed before each replay)")
@@ -441,6 +444,8 @@ def main():
         spec = inputs.with_state_dtype(spec, args.state_dtype)
     if args.conv_kernel:
         spec = inputs.with_conv(spec, args.conv_kernel)
+    if args.pad_ssm_to_kv_page:
+        spec = inputs.with_padded_blocks(spec)
     wl = WORKLOADS[args.workload]
     args.batch = wl["batch"] if args.batch is None else args.batch
     args.seed = wl["seed"] if args.seed is None else args.seed
@@ -721,6 +726,7 @@ def main():
                                % (wl["text"], sc.batch, churn_kv, churn_ssm, mig_pages),
                    "name": args.workload, "batch": sc.batch, "seed": args.seed,
                    "ssm_state_dtype": args.state_dtype, "ssm_conv_kernel": args.conv_kernel,
+                   "ssm_pad_to_kv_page": bool(args.pad_ssm_to_kv_page),
                    "decode_from_hip_graph": bool(args.graph),
                    "arena_backing": args.backing if vmm_chunk is None
                    else "vmm, %d KiB chunks" % args.vmm_chunk_kib,

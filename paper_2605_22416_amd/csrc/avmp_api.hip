@@ -18,6 +18,9 @@ namespace {
 
 thread_local std::string g_last_error;
 
+constexpr const char* kDeadPools =
+    "a device call failed half way through a migration: these pools can only be destroyed";
+
 int fail(int code, const char* what) {
   g_last_error = what;
   return code;
@@ -160,8 +163,12 @@ struct avmp_pools {
     if (!prof_free.empty()) {
       r = prof_free.back();
       prof_free.pop_back();
-    } else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) {
-      return -1;
+    } else {
+      if (hipEventCreate(&r.a) != hipSuccess) return -1;
+      if (hipEventCreate(&r.b) != hipSuccess) {
+        (void)hipEventDestroy(r.a);
+        return -1;
+      }
     }
     r.kind = kind;
     (void)hipEventRecord(r.a, s);
@@ -243,7 +250,7 @@ struct ProfScope {
 // Queue -> device: table entries (coalesced to the last value per index, so the
 // scatter has no ordering hazard) and zero fills of freshly allocated SSM blocks.
 int flush_pending(avmp_pools* p, hipStream_t s) {
-  if (p->dead) return fail(AVMP_ERR_DEVICE, "a device call failed half way through a migration: these pools can only be destroyed");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, kDeadPools);
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
   if (p->pending.empty() && p->pending_zero.empty()) return AVMP_OK;
   std::vector<avmp::TableUpdate> upd;
@@ -341,7 +348,7 @@ uint32_t roomy_pages(uint32_t max_pages) {
 int check_step(avmp_pools* p, const avmp_step_t* st, uint32_t* n_attn_out, uint32_t* n_ssm_out) {
   if (p == nullptr || st == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null argument");
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
-  if (p->dead) return fail(AVMP_ERR_DEVICE, "a device call failed half way through a migration: these pools can only be destroyed");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, kDeadPools);
   if (st->n_layers != 0 && st->layer_kind == nullptr) return fail(AVMP_ERR_INVALID_ARG, "layer_kind");
   uint32_t n_attn = 0, n_ssm = 0;
   for (uint32_t i = 0; i < st->n_layers; ++i) {
@@ -674,6 +681,7 @@ int avmp_alloc_auto(avmp_pools_t* p, int pool, uint32_t n, avmp_handle_t* out, v
 
 int avmp_absorb_gap(avmp_pools_t* p, int pool, avmp_migrate_result_t* out) {
   if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
+  if (p->dead) return fail(AVMP_ERR_DEVICE, kDeadPools);
   uint32_t gain = 0;
   uint64_t wasted = 0;
   const int rc = p->st.absorb_gap(pool, &gain, &wasted);
@@ -696,6 +704,7 @@ int avmp_flush(avmp_pools_t* p, void* stream) {
 int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migrate_result_t* out) {
   if (p == nullptr) return fail(AVMP_ERR_INVALID_ARG, "null pools");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->dead) return fail(AVMP_ERR_DEVICE, kDeadPools);
   if (p->has_device && (donor == 0 || donor == 1) && n != 0 &&
       (p->pending_entries || !p->pending_zero.empty())) {
     // queued zero fills and table entries refer to the geometry before the move (the copy
@@ -740,7 +749,11 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
       }
       moved += k;
     }
-    HIP_TRY(p->staging.release_after(b, s));
+    const hipError_t e = p->staging.release_after(b, s);
+    if (e != hipSuccess) {
+      p->dead = true;
+      return fail_hip(e, "avmp_migrate: event behind the move list");
+    }
   } else {
     std::vector<avmp::Move> moves(n);
     for (uint32_t k; (k = p->st.migrate_moves(moves.data() + moved, n - moved)) != 0;) moved += k;
@@ -931,14 +944,20 @@ int avmp_profile_read(avmp_pools_t* p, void* stream, avmp_profile_t* out) {
   if (!p->has_device) return fail(AVMP_ERR_DEVICE, "pools have no device arena");
   HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
   std::memset(out, 0, sizeof(*out));
-  for (const auto& r : p->prof) {
+  hipError_t first_error = hipSuccess;
+  for (const auto& r : p->prof) {           // every pair goes back to the free list, whatever happens
     float ms = 0.f;
-    HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
-    out->ms[r.kind] += double(ms);
-    out->launches[r.kind] += 1;
+    const hipError_t e = hipEventElapsedTime(&ms, r.a, r.b);
+    if (e == hipSuccess) {
+      out->ms[r.kind] += double(ms);
+      out->launches[r.kind] += 1;
+    } else if (first_error == hipSuccess) {
+      first_error = e;
+    }
     p->prof_free.push_back(r);
   }
   p->prof.clear();
+  if (first_error != hipSuccess) return fail_hip(first_error, "hipEventElapsedTime");
   return AVMP_OK;
 }
 
