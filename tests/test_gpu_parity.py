@@ -543,6 +543,7 @@ def test_decode_loop_with_widening_handle_rows_allocates_the_work_buffer_once():
     ("bf16", 4, 2, 32, 2, 8, 4),        # head_dim 32: vector-ALU attention kernel on bf16; dstate 4
     ("bf16", 32, 1, 128, 2, 128, 128),  # query group of 32 > 16: vector-ALU kernel; headdim 128 (two passes)
     ("f32", 6, 3, 48, 3, 20, 32),       # fp32, odd head_dim
+    ("f32", 40, 2, 32, 2, 8, 8),        # query group of 20: a full and a partly filled workgroup per KV head
 ])
 def test_other_head_shapes(dtype, Hq, G, D, H, P, N):
     """Every kernel instantiation and dispatch branch, on shapes other than the
