@@ -588,10 +588,10 @@ def main():
                "p90": float(np.percentile(per_step_us, 90)), "min": float(per_step_us.min()),
                "max": float(per_step_us.max())}
     # the same `steps` steps again with a HIP event pair around every kernel launch (on the
-    # launch stream): per-kernel durations for the roofline.  The event pairs cost about 10 us
+    # launch stream): per-kernel durations for the roofline.  The event pairs cost a few us
     # per launch, which is why the headline region above runs without them.
     events = not args.no_kernel_events
-    wall_ev, prof = None, {}
+    wall_ev, prof, empty_pair_us = None, {}, None
     if events:
         replay[0] = False                 # per-kernel events need eager launches
         av.avmp_profile_enable(ses.p, True)
@@ -604,6 +604,15 @@ def main():
         wall_ev = time.perf_counter() - t0
         rc, prof = av.avmp_profile_read(ses.p, stream)
         av.avmp_profile_enable(ses.p, False)
+        # what such a pair reads with nothing between its two records: the share of every
+        # per-kernel figure below that is the measurement, not the kernel
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                 for _ in range(64)]
+        for ea, eb in pairs:
+            ea.record(stream)
+            eb.record(stream)
+        torch.cuda.synchronize()
+        empty_pair_us = float(np.median([ea.elapsed_time(eb) * 1e3 for ea, eb in pairs]))
     copies[0] = copies_timed
     rc, faults = av.avmp_device_faults(ses.p)
     assert rc == av.AVMP_OK and faults == 0, "untranslatable handles: %d" % faults
@@ -641,9 +650,9 @@ def main():
                     "avg_launch_us": kernels["ssm"]["avg_us"]}
     roofline_attention = None
     if "attention" in kernels:
-        # everything an attention layer launches: the attention kernel (which merges its own
-        # partial results), the separate merge where the vector-ALU path runs, and the layer's
-        # share of the once-per-step preparation (run plan + translation of all KV handles)
+        # everything an attention layer launches: the attention kernel, the merge of its partial
+        # results, and the layer's share of the once-per-step preparation (run plan + translation
+        # of all KV handles)
         parts = {"attention": kernels["attention"]["avg_us"]}
         if "attention_merge" in kernels:
             parts["attention_merge"] = kernels["attention_merge"]["avg_us"]
@@ -653,7 +662,7 @@ def main():
                                                 / kernels["attention"]["launches"])
         layer_us = sum(parts.values())
         a = attn_layer_bytes / (layer_us * 1e-6) / 1e9
-        roofline_attention = {"kernel": "attn_mfma_kernel + attn_prepare_kernel / attention layers",
+        roofline_attention = {"kernel": "attention kernel + merge kernel + attn_prepare_kernel / attention layers",
                               "bound": "hbm", "achieved": a,
                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
                               "traffic": measured_traffic("attention", sc.batch, args.workload, args.seed),
@@ -732,6 +741,7 @@ def main():
                    else "vmm, %d KiB chunks" % args.vmm_chunk_kib,
                    "arena_GB": sc.arena_bytes / 1e9},
         "ms_per_step_with_kernel_events": (wall_ev / args.steps * 1e3) if wall_ev else None,
+        "empty_event_pair_us": empty_pair_us,
         "algorithmic_bytes_per_step": step_bytes,
         "migrated_pages_per_s": 2 * mig_pages * args.steps / wall,
         "kernels": kernels, "migration_sweep": sweep, "migration_sweep_capacity": sweep_capacity,
