@@ -42,7 +42,10 @@ KERNEL_MATCH = {"ssm": ("ssm_update_kernel",), "attention": ("attn_mfma_kernel",
 
 
 def source_digest(kind):
+    """Digest of a kernel's source as the compiler sees it: comments and white space do not
+    count, so rewording a comment does not retire a measurement."""
     import hashlib
+    import re
     name, start, stop = KERNEL_SOURCES[kind]
     try:
         text = open(os.path.join(ROOT, "paper_2605_22416_amd", "csrc", name)).read()
@@ -50,7 +53,9 @@ def source_digest(kind):
             text = text[text.index(start):text.index(stop)]
     except (OSError, ValueError):
         return None
-    return hashlib.sha256(text.encode()).hexdigest()[:16]
+    text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+    text = re.sub(r"//[^\n]*", " ", text)          # the sources hold no "//" inside string literals
+    return hashlib.sha256(" ".join(text.split()).encode()).hexdigest()[:16]
 
 
 def measured_traffic(kind, batch, workload, seed):
