@@ -145,7 +145,7 @@ typedef struct avmp_stats {
  * resident; the step appends the new token only if k_new / v_new are given.
  * Two requests of one batch must not name the same SSM handle. */
 typedef struct avmp_step {
-  uint32_t batch;
+  uint32_t batch;                    /* at most 65535; with attention layers, batch x max_pages < 2^31 */
   uint32_t n_layers;
   const uint8_t* layer_kind;         /* host [n_layers]: AVMP_LAYER_* */
   uint32_t max_pages;                /* row stride of kv_handles; >= ceil(max ctx / 16) */

@@ -82,25 +82,32 @@ __device__ __forceinline__ uint32_t pages_of(uint32_t ctx, uint32_t max_pages) {
   return n > max_pages ? max_pages : n;      // a context beyond the handle row is clamped
 }
 
-constexpr uint32_t kMinRunPages = 4;
-// What starting a request costs a wavefront, in pages' worth of time: the query load
-// that waits on the request index, the refill of the page pipeline, the output row.
-// Measured per layer with 2 / 3 / 5 / 8: a batch of 256 requests, half of them 1-4 pages
-// long, 64.7 / 62.8 / 59.9 / 62.1 us; 64 requests of 8-128 pages 48.5 / 49.5 / 49.1 / 49.6 us
-// (a run there holds one or two starts, and their cost hides behind other wavefronts' loads).
-constexpr uint32_t kRequestCost = 5;
+// What a request costs the wavefronts that walk it, in pages' worth of time: its pages, but
+// never less than kRequestFloor (a request of one page still waits for its query rows, fills
+// the page pipeline and writes its output rows, and a wavefront that crosses many such
+// requests is bound by those waits), plus kRequestCost for the start.  A request without
+// pages costs nothing: no wavefront visits it.  Measured per layer (floor, start) = (6, 2) /
+// (6, 1) / (8, 1) / (4, 2) / (8, 0), and pages + 5 for every request: 256 requests, half of
+// them 1-4 pages long, 59.3 / 60.3 / 59.9 / 61.7 / 60.6, and 59.9 us; 64 requests of 8-128
+// pages 48.2 / 48.5 / 48.7 / 48.6 / 49.9, and 49.1 us.
+constexpr uint32_t kRequestFloor = 6;
+constexpr uint32_t kRequestCost = 2;
+__host__ __device__ __forceinline__ uint32_t request_cost(uint32_t pages) {
+  if (pages == 0) return 0;
+  return (pages < kRequestFloor ? kRequestFloor : pages) + kRequestCost;
+}
 
 // Preparation of a decode step's attention layers, one launch.
 //
-// Block 0 is the plan.  It computes the page prefix sums over the batch and cuts the
-// batch's page sequence into runs of equal COST: request r costs kRequestCost + its
-// pages; on the cost axis it sits at prefix[r] + kRequestCost * r, its page p at that
-// + kRequestCost + p.  Run w takes the pages whose position falls into
-// [w * cpw, (w + 1) * cpw): as pages they are still one contiguous stretch of the
-// batch's page sequence, so desc[w] = (first request, first page in it, first and
-// one-past-last index in that sequence).  plan[0] = total pages, plan[1] = cost per
-// run (cpw).  It also writes the zero output rows of requests without resident
-// tokens and counts contexts that exceed the handle row.
+// Block 0 is the plan.  It computes, over the batch, the prefix sums of the requests' pages
+// and of their costs (request_cost), and cuts the cost axis into runs of equal length cpw.
+// Request r sits at pos[r] on that axis; what it costs beyond its pages comes first, then
+// its pages, one unit each.  Run w takes the pages whose position falls into
+// [w * cpw, (w + 1) * cpw): as pages they are still one contiguous stretch of the batch's
+// page sequence, so desc[w] = (first request, first page in it, first and one-past-last
+// index in that sequence).  plan[0] = total pages, plan[1] = cpw.  It also writes the zero
+// output rows of requests without resident tokens and counts contexts that exceed the
+// handle row.
 //
 // Every other block translates 256 entries of the handle tables of all attention
 // layers: slots[layer][r][page] = physical slot (0xFFFFFFFF if the handle does not
@@ -113,7 +120,8 @@ struct PrepareArgs {
   const uint32_t* handles;    // [n_attn][batch][max_pages]
   uint32_t* slots;            // [n_attn][batch][max_pages] out
   uint32_t* plan;             // [2] out
-  uint32_t* prefix;           // [batch + 1] out
+  uint32_t* prefix;           // [batch + 1] out: pages before each request
+  uint32_t* pos;              // [batch + 1] out: cost before each request
   uint4* desc;                // [runs] out
   float* o;                   // [n_attn][batch][n_q_heads * head_dim]: rows of empty requests
   uint32_t batch, max_pages, runs, append, n_attn, row_floats;
@@ -121,45 +129,52 @@ struct PrepareArgs {
 };
 
 __device__ void plan_block(const PrepareArgs& a) {
-  __shared__ uint32_t sums[1024];      // inclusive page sums at the end of each thread's segment
-  __shared__ uint32_t wave_sums[16];
+  // per thread: (cost << 32 | pages) summed over its segment of the batch, inclusive
+  __shared__ uint64_t sums[1024];
+  __shared__ uint64_t wave_sums[16];
   const uint32_t tid = threadIdx.x, batch = a.batch, runs = a.runs;
   const uint32_t seg = (batch + 1023) / 1024;
   const uint32_t lo = min(batch, tid * seg), hi = min(batch, lo + seg);
-  uint32_t local = 0;
-  for (uint32_t r = lo; r < hi; ++r) local += pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
+  auto packed = [&](uint32_t r) -> uint64_t {
+    const uint32_t pg = pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
+    return (uint64_t(request_cost(pg)) << 32) | pg;
+  };
+  uint64_t local = 0;
+  for (uint32_t r = lo; r < hi; ++r) local += packed(r);
   // inclusive scan over the 1024 threads: inside each wavefront, then over the 16 wavefronts
-  uint32_t incl = local;
+  uint64_t incl = local;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t up = __shfl_up(incl, off);
+    const uint64_t up = __shfl_up(incl, off);
     if ((tid & 63u) >= uint32_t(off)) incl += up;
   }
   if ((tid & 63u) == 63u) wave_sums[tid >> 6] = incl;
   __syncthreads();
   for (uint32_t wv = 0; wv < (tid >> 6); ++wv) incl += wave_sums[wv];
   sums[tid] = incl;
-  uint32_t run = incl - local;                              // exclusive start of this segment
+  uint64_t run = incl - local;                              // exclusive start of this segment
   for (uint32_t r = lo; r < hi; ++r) {
-    a.prefix[r] = run;
-    run += pages_of(attended_tokens(a.ctx, r, a.append), a.max_pages);
+    a.prefix[r] = uint32_t(run);
+    a.pos[r] = uint32_t(run >> 32);
+    run += packed(r);
   }
-  __syncthreads();                                          // sums[] and prefix[] visible to the block
-  const uint32_t total = sums[1023];
-  const uint64_t total_cost = uint64_t(total) + uint64_t(kRequestCost) * batch;
-  // equal shares, but room for at least kMinRunPages pages: with few pages in the batch,
-  // shorter runs would only add partial results to merge
-  const uint64_t cpw = max(uint64_t(kMinRunPages + kRequestCost), (total_cost + runs - 1) / runs);
+  __syncthreads();                                          // sums[], prefix[], pos[] visible to the block
+  const uint32_t total = uint32_t(sums[1023]);
+  const uint64_t total_cost = sums[1023] >> 32;
+  // equal shares, but never shorter than the least a request costs: with few pages in the
+  // batch, shorter runs would only add partial results to merge
+  const uint64_t cpw = max(uint64_t(kRequestFloor + kRequestCost), (total_cost + runs - 1) / runs);
   if (tid == 0) {
     a.prefix[batch] = total;
+    a.pos[batch] = uint32_t(total_cost);
     a.plan[0] = total;
     a.plan[1] = uint32_t(cpw);
   }
-  // pages before request r: up to 1024 requests every thread's segment is one request and the
-  // sums in shared memory answer; beyond that the array just written does
-  auto pages_before = [&](uint32_t r) -> uint32_t {
-    if (seg == 1) return r == 0 ? 0u : sums[r - 1];
-    return a.prefix[r];
+  // pages and cost before request r: up to 1024 requests every thread's segment is one request
+  // and the sums in shared memory answer; beyond that the arrays just written do
+  auto before = [&](uint32_t r) -> uint64_t {
+    if (seg == 1) return r == 0 ? 0ull : sums[r - 1];
+    return (uint64_t(a.pos[r]) << 32) | a.prefix[r];
   };
   // first page at or after cost position c: (request, page in it, index in the page sequence)
   auto first_page_at = [&](uint64_t c, uint32_t* rq, uint32_t* pg) -> uint32_t {
@@ -168,18 +183,22 @@ __device__ void plan_block(const PrepareArgs& a) {
       *pg = 0;
       return total;
     }
-    // last r whose cost position prefix[r] + kRequestCost * r is <= c
+    // last r whose position is <= c; requests without pages have no width, so this is never
+    // one of them (c < total_cost: a request with pages follows any such position)
     uint32_t lo_r = 0, hi_r = batch;
     while (hi_r - lo_r > 1) {
       const uint32_t mid = (lo_r + hi_r) / 2;
-      if (uint64_t(pages_before(mid)) + uint64_t(kRequestCost) * mid <= c) lo_r = mid; else hi_r = mid;
+      if ((before(mid) >> 32) <= c) lo_r = mid; else hi_r = mid;
     }
-    const uint32_t before = pages_before(lo_r);
-    const uint64_t at = uint64_t(before) + uint64_t(kRequestCost) * lo_r + kRequestCost;   // its page 0
-    const uint32_t p = c > at ? uint32_t(c - at) : 0;       // c < position of request lo_r + 1, so p < its pages
-    *rq = lo_r;                                             // (or p = 0 in a request without pages: the
-    *pg = p;                                                //  walk skips it)
-    return before + p;
+    const uint64_t here = before(lo_r);
+    const uint64_t next = lo_r + 1 < batch ? before(lo_r + 1) : sums[1023];
+    const uint32_t pages = uint32_t(next) - uint32_t(here);
+    // its page 0 sits behind what the request costs beyond its pages
+    const uint64_t at = (here >> 32) + (request_cost(pages) - pages);
+    const uint32_t p = c > at ? uint32_t(c - at) : 0;       // c < position of the next request, so p < pages
+    *rq = lo_r;
+    *pg = p;
+    return uint32_t(here) + p;
   };
   for (uint32_t w = tid; w < runs; w += 1024) {
     uint32_t r0, p0, r1, p1;
@@ -189,7 +208,7 @@ __device__ void plan_block(const PrepareArgs& a) {
   }
   // requests without resident tokens get zero rows; a context beyond the handle row is counted
   __shared__ uint32_t n_empty;
-  uint32_t* const empties = sums;                           // the scan is done with it
+  uint32_t* const empties = reinterpret_cast<uint32_t*>(sums);   // the scan is done with it (room for 2048)
   __syncthreads();
   if (tid == 0) n_empty = 0;
   __syncthreads();
@@ -569,9 +588,10 @@ __global__ __launch_bounds__(256) void attn_merge_runs_kernel(AttnLaunch a) {
   const uint32_t g = blockIdx.x, r = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint32_t n_waves = blockDim.x >> 6;
   const uint32_t start = a.prefix[r], end = a.prefix[r + 1];
+  const uint64_t pos = a.pos[r];
   if (start == end) return;                 // no resident tokens: the plan wrote the zero rows
   const uint64_t cpw = a.plan[1];
-  const uint64_t at = uint64_t(start) + uint64_t(kRequestCost) * r + kRequestCost;
+  const uint64_t at = pos + (request_cost(end - start) - (end - start));      // position of its page 0
   const uint32_t wa = uint32_t(at / cpw), wb = uint32_t((at + (end - start) - 1) / cpw);
   if (wa == wb) return;                     // one run covered it and wrote the rows
   const uint32_t np = wb - wa + 1, Gq = a.n_q_heads / a.n_kv_heads;
@@ -607,6 +627,7 @@ hipError_t launch_attention_prepare(const AttnLaunch& a, const uint32_t* handles
   p.slots = slots_all;
   p.plan = const_cast<uint32_t*>(a.plan);
   p.prefix = const_cast<uint32_t*>(a.prefix);
+  p.pos = const_cast<uint32_t*>(a.pos);
   p.desc = const_cast<uint4*>(a.desc);
   p.o = o_all;
   p.batch = a.batch;

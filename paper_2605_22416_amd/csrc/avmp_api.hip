@@ -310,7 +310,7 @@ WorkLayout work_layout(const avmp_config_t& c, uint32_t n_attn, uint32_t n_ssm, 
                          : size_t(batch) * L.max_chunks * c.n_q_heads;
     L.part_floats = (L.part_rows * (size_t(c.head_dim) + 2) + 3) / 4 * 4;   // keeps the plan 16-byte aligned
     L.prefix_words = (size_t(batch) + 4) / 4 * 4;                           // batch + 1 entries
-    L.plan_words = 4 + L.prefix_words + size_t(L.runs) * 4;
+    L.plan_words = 4 + 2 * L.prefix_words + size_t(L.runs) * 4;           // plan, page and cost prefix sums, runs
     L.slot_cap = size_t(batch) * max_pages;                                 // per attention layer
     L.slot_words = L.mfma ? size_t(n_attn) * L.slot_cap : 0;
   }
@@ -357,6 +357,8 @@ int check_step(avmp_pools* p, const avmp_step_t* st, uint32_t* n_attn_out, uint3
     else return fail(AVMP_ERR_INVALID_ARG, "unknown layer kind");
   }
   if (st->batch > 65535) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
+  if (n_attn && uint64_t(st->batch) * st->max_pages > 0x7FFFFFFFull)      // page counts are summed in 32 bits
+    return fail(AVMP_ERR_INVALID_ARG, "batch x max_pages above 2^31 - 1");
   if (n_attn && st->batch &&
       (!st->kv_handles || !st->ctx || !st->q || !st->o || st->max_pages == 0))
     return fail(AVMP_ERR_INVALID_ARG, "attention layers need kv_handles, ctx, q, o, max_pages");
@@ -406,7 +408,8 @@ int run_step(avmp_pools* p, const avmp_step_t* st, hipStream_t s, uint32_t n_att
       if (mfma) {
         a.plan = plan_base;
         a.prefix = plan_base + 4;
-        a.desc = reinterpret_cast<const uint4*>(plan_base + 4 + L.prefix_words);
+        a.pos = plan_base + 4 + L.prefix_words;
+        a.desc = reinterpret_cast<const uint4*>(plan_base + 4 + 2 * L.prefix_words);
         a.runs = L.runs;
         a.slots = slots_base + size_t(ia) * L.slot_cap;
       }

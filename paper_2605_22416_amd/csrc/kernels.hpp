@@ -27,6 +27,7 @@ struct AttnLaunch {
   // matrix-core path only: balanced runs (see attn_mfma.hip)
   const uint32_t* plan;      // device [2]: total pages, cost per run
   const uint32_t* prefix;    // device [batch + 1]: page prefix sums
+  const uint32_t* pos;       // device [batch + 1]: cost prefix sums (the axis the runs are cut on)
   const uint4* desc;         // device [runs]: each run's first (request, page) and its stretch
                              // [first, last) of the batch's page sequence
   const uint32_t* slots;     // device [batch][max_pages]: this layer's pre-translated slots

@@ -192,6 +192,13 @@ def test_empty_batch_and_zero_context():
     assert not o[0, 0].any() and not o[0, 2].any()
     st, keep = av.make_step(0, spec.layer_kinds, 1, *([None] * 11))
     assert av.avmp_decode_step(g.p, st) == av.AVMP_OK        # empty batch: nothing to do
+    # a step whose page counts could not be summed in 32 bits is refused before anything runs
+    st, keep = av.make_step(65535, spec.layer_kinds, 1 << 16, *([None] * 11))
+    assert av.avmp_decode_step(g.p, st) == av.AVMP_ERR_INVALID_ARG
+    assert "max_pages" in av.avmp_last_error()
+    st, keep = av.make_step(65536, spec.layer_kinds, 1, *([None] * 11))
+    assert av.avmp_decode_step(g.p, st) == av.AVMP_ERR_INVALID_ARG
+    assert "65535" in av.avmp_last_error()
     g.close()
 
 
