@@ -261,6 +261,25 @@ int flush_pending(avmp_pools* p, hipStream_t s) {
     upd.reserve(last.size());
     for (const auto& kv : last) upd.push_back({kv.first, kv.second});
   }
+  if (upd.size() <= avmp::kInlineUpdates && p->pending_zero.size() <= avmp::kInlineZero) {
+    // short lists (a decode step's churn) ride in the kernel arguments: one launch, no staging
+    avmp::InlineFlush f{};
+    f.P = p->dev_view();
+    f.table = p->table_dev;
+    f.n_upd = uint32_t(upd.size());
+    f.n_zero = uint32_t(p->pending_zero.size());
+    f.ssm_capacity = p->st.capacity(AVMP_POOL_SSM);
+    if (f.n_upd) std::memcpy(f.upd, upd.data(), upd.size() * sizeof(avmp::TableUpdate));
+    if (f.n_zero) std::memcpy(f.zero, p->pending_zero.data(), p->pending_zero.size() * sizeof(uint32_t));
+    {
+      ProfScope scope(p, p->profiling, AVMP_K_TABLE, s);
+      HIP_TRY(avmp::launch_flush_inline(f, s));
+    }
+    p->pending.clear();
+    p->pending_zero.clear();
+    p->pending_entries = false;
+    return AVMP_OK;
+  }
   const size_t upd_bytes = upd.size() * sizeof(avmp::TableUpdate);
   const size_t zero_bytes = p->pending_zero.size() * sizeof(uint32_t);
   Staging::Buf* b = nullptr;
@@ -721,7 +740,24 @@ int avmp_migrate(avmp_pools_t* p, int donor, uint32_t n, void* stream, avmp_migr
   // from here on nothing can fail but a HIP call
   uint32_t moved = 0;
   const bool exchange = p->has_device && p->remap != nullptr && p->remappable[donor];
-  if (p->has_device && !exchange) {
+  if (p->has_device && !exchange && n <= avmp::kInlineMoves) {
+    // a short migration (the policy's default batch): the whole move list rides in the
+    // arguments of one copy launch
+    avmp::InlineMoves im{};
+    moved = p->st.migrate_moves(im.mv, n);          // at most n units move
+    if (moved != 0) {
+      im.P = p->dev_view();
+      im.table = p->table_dev;
+      im.pool = donor;
+      im.n = moved;
+      ProfScope scope(p, p->profiling, AVMP_K_MIGRATE_COPY, s);
+      const hipError_t e = avmp::launch_migrate_copy_inline(im, s);
+      if (e != hipSuccess) {
+        p->dead = true;
+        return fail_hip(e, "avmp_migrate: copy launch");
+      }
+    }
+  } else if (p->has_device && !exchange) {
     // The moves are planned straight into pinned memory, a slice at a time, and each slice's
     // copy is launched before the next is planned: the device copies while the host plans.
     // The copy kernel rewrites the table entries of the units it moves.

@@ -23,10 +23,8 @@ __global__ void table_update_kernel(uint32_t* __restrict__ table,
   if (i < n) table[upd[i].index] = upd[i].slot;
 }
 
-__global__ __launch_bounds__(256) void zero_units_kernel(DevPools P, int pool,
-                                                         const uint32_t* __restrict__ slots) {
-  const uint32_t slot = slots[blockIdx.y];
-  if (slot >= P.capacity[pool]) return;     // freed and migrated away before the flush
+// one workgroup's share of clearing a unit (the grid's x dimension shares the unit out)
+__device__ __forceinline__ void zero_unit(const DevPools& P, int pool, uint32_t slot) {
   const uint64_t off = pool == 0 ? uint64_t(slot) * P.unit[0]
                                  : P.usable - (uint64_t(slot) + 1) * P.unit[1];
   uint4* dst = reinterpret_cast<uint4*>(P.arena + off);
@@ -35,6 +33,28 @@ __global__ __launch_bounds__(256) void zero_units_kernel(DevPools P, int pool,
   // plain stores: with the non-temporal hint this fill measured 24.5 us against 22.4 us
   for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += uint64_t(gridDim.x) * 256)
     dst[i] = z;
+}
+
+__global__ __launch_bounds__(256) void zero_units_kernel(DevPools P, int pool,
+                                                         const uint32_t* __restrict__ slots) {
+  const uint32_t slot = slots[blockIdx.y];
+  if (slot >= P.capacity[pool]) return;     // freed and migrated away before the flush
+  zero_unit(P, pool, slot);
+}
+
+// A flush whose lists fit the kernel arguments, one launch: rows 0 .. n_zero-1 of the grid
+// clear one SSM block each, the row behind them writes the table entries.  The two do not
+// touch the same memory; the capacity a slot is checked against is the host's (the device's
+// copy may be among the entries being written).
+__global__ __launch_bounds__(256) void flush_inline_kernel(InlineFlush f) {
+  if (blockIdx.y == f.n_zero) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < f.n_upd) f.table[f.upd[i].index] = f.upd[i].slot;
+    return;
+  }
+  const uint32_t slot = f.zero[blockIdx.y];
+  if (slot >= f.ssm_capacity) return;
+  zero_unit(f.P, 1, slot);
 }
 
 __global__ void translate_kernel(DevPools P, const uint32_t* __restrict__ handles, uint32_t n,
@@ -53,9 +73,8 @@ __global__ void translate_kernel(DevPools P, const uint32_t* __restrict__ handle
 // Source slots lie at or above the new capacity and destinations below it, so
 // no two copies overlap.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t* __restrict__ table,
-                                                           int pool, const Move* __restrict__ moves) {
-  const Move mv = moves[blockIdx.y];
+__device__ __forceinline__ void copy_unit(const DevPools& P, uint32_t* __restrict__ table, int pool,
+                                          const Move mv) {
   const uint64_t unit = P.unit[pool];
   const uint64_t so = pool == 0 ? uint64_t(mv.src_slot) * unit : P.usable - (uint64_t(mv.src_slot) + 1) * unit;
   const uint64_t dof = pool == 0 ? uint64_t(mv.dst_slot) * unit : P.usable - (uint64_t(mv.dst_slot) + 1) * unit;
@@ -79,6 +98,16 @@ __global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t*
   }
   for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
   if (blockIdx.x == 0 && threadIdx.x == 0) table[P.vid_base[pool] + mv.vid] = mv.dst_slot;
+}
+
+__global__ __launch_bounds__(256) void migrate_copy_kernel(DevPools P, uint32_t* __restrict__ table,
+                                                           int pool, const Move* __restrict__ moves) {
+  copy_unit(P, table, pool, moves[blockIdx.y]);
+}
+
+// the same with the move list in the kernel arguments (short migrations)
+__global__ __launch_bounds__(256) void migrate_copy_inline_kernel(InlineMoves m) {
+  copy_unit(m.P, m.table, m.pool, m.mv[blockIdx.y]);
 }
 
 // ---------------------------------------------------------------------------
@@ -334,6 +363,28 @@ hipError_t launch_zero_units(const DevPools& P, int pool, const uint32_t* slots,
     const uint32_t cnt = n - done < 65535 ? n - done : 65535;
     zero_units_kernel<<<dim3(gx, cnt), dim3(256), 0, s>>>(P, pool, slots + done);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_flush_inline(const InlineFlush& f, hipStream_t s) {
+  if (f.n_upd == 0 && f.n_zero == 0) return hipSuccess;
+  if (f.n_upd > kInlineUpdates || f.n_zero > kInlineZero) return hipErrorInvalidValue;
+  const uint64_t n16 = f.P.unit[1] / 16;
+  uint32_t gx = f.n_zero ? uint32_t((n16 + 256 * 8 - 1) / (256 * 8)) : 1;
+  const uint32_t ux = (f.n_upd + 255) / 256;
+  if (gx < ux) gx = ux;
+  if (gx == 0) gx = 1;
+  flush_inline_kernel<<<dim3(gx, f.n_zero + 1), dim3(256), 0, s>>>(f);
+  return hipGetLastError();
+}
+
+hipError_t launch_migrate_copy_inline(const InlineMoves& m, hipStream_t s) {
+  if (m.n == 0) return hipSuccess;
+  if (m.n > kInlineMoves || (m.pool != 0 && m.pool != 1)) return hipErrorInvalidValue;
+  const uint64_t n16 = m.P.unit[m.pool] / 16;
+  uint32_t gx = uint32_t((n16 + 256 * 4 - 1) / (256 * 4));    // 16 KiB per workgroup
+  if (gx == 0) gx = 1;
+  migrate_copy_inline_kernel<<<dim3(gx, m.n), dim3(256), 0, s>>>(m);
   return hipGetLastError();
 }
 

@@ -62,6 +62,34 @@ struct ConvLaunch {
   uint32_t dtype;            // element type of u, taps, bias and the window: 0 f32, 1 bf16
 };
 
+// Short lists travel inside the kernel arguments instead of pinned staging memory: nothing to
+// keep alive behind the launch, so no event, and one launch for a flush's table entries and
+// zero fills.  Sized to stay under the 4 KiB a launch may carry.
+constexpr uint32_t kInlineUpdates = 416, kInlineZero = 64, kInlineMoves = 300;
+
+struct InlineFlush {
+  DevPools P;
+  uint32_t* table;
+  uint32_t n_upd, n_zero;
+  uint32_t ssm_capacity;            // the host's value at the flush: slots at or beyond it are not cleared
+  uint32_t pad_;
+  TableUpdate upd[kInlineUpdates];  // coalesced: one entry per index
+  uint32_t zero[kInlineZero];       // SSM slots to clear
+};
+static_assert(sizeof(InlineFlush) <= 4096, "kernel arguments are limited to 4 KiB");
+
+struct InlineMoves {
+  DevPools P;
+  uint32_t* table;
+  int pool;
+  uint32_t n;
+  Move mv[kInlineMoves];
+};
+static_assert(sizeof(InlineMoves) <= 4096, "kernel arguments are limited to 4 KiB");
+
+hipError_t launch_flush_inline(const InlineFlush& f, hipStream_t s);
+hipError_t launch_migrate_copy_inline(const InlineMoves& m, hipStream_t s);
+
 bool conv_supported(uint32_t dtype, uint32_t taps_k, uint32_t heads, uint32_t headdim,
                     uint32_t dstate);
 hipError_t launch_conv_update(const ConvLaunch& a, hipStream_t s);
