@@ -264,6 +264,52 @@ def test_migration_moves_live_units_bit_exactly_both_directions(backing):
     g.close()
 
 
+@pytest.mark.parametrize("n_kv,n_ssm,n_mig", [(352, 64, 300), (353, 64, 301), (351, 65, 300)])
+def test_update_lists_on_both_sides_of_the_kernel_argument_limits(n_kv, n_ssm, n_mig):
+    """A flush of up to 416 table entries and 64 blocks to clear, and a migration of up to
+    300 units, send their lists inside the kernel arguments; one more of any of them goes
+    through pinned staging memory.  Either way the device table, the cleared blocks and the
+    moved units must come out the same: exactly at the limits, and one beyond each."""
+    from paper_2605_22416_amd import binding as av
+    spec = inputs.TINY
+    rng = np.random.default_rng(n_kv + n_ssm + n_mig)
+    sc = inputs.make_scenario(spec, "tiny", 1, seed=77, ctx=[16], headroom=1500.0)
+    op, g, kv, ssm = _both(sc, poison=True)
+    rc_o, new_kv_o = op.alloc(0, n_kv)
+    rc_g, new_kv = av.avmp_alloc(g.p, 0, n_kv)
+    assert rc_o == orc.OK and rc_g == av.AVMP_OK and list(new_kv) == list(new_kv_o)
+    rc_o, new_ssm_o = op.alloc(1, n_ssm)
+    rc_g, new_ssm = av.avmp_alloc(g.p, 1, n_ssm)
+    assert rc_o == orc.OK and rc_g == av.AVMP_OK and list(new_ssm) == list(new_ssm_o)
+    assert av.avmp_flush(g.p) == av.AVMP_OK            # n_kv + n_ssm entries, n_ssm blocks to clear
+    everything = [int(h) for h in list(new_kv) + list(new_ssm) + list(kv.reshape(-1)) + list(ssm.reshape(-1))]
+    _check_translation(g, op, everything)
+    for h in new_ssm:
+        assert not g.read_unit(int(h)).any()           # fresh blocks read as zero ...
+    for h in rng.choice(np.asarray(new_kv), size=8, replace=False):
+        assert (g.read_unit(int(h)) == 0xFF).all()     # ... and nothing else was cleared
+    # distinct bytes in every new page, then KV capacity leaves from under the live ones
+    contents = {}
+    for h in new_kv:
+        data = rng.integers(0, 256, size=spec.kv_page_bytes, dtype=np.uint8)
+        g.write_unit(int(h), data)
+        op.unit_view(int(h))[:] = data
+        contents[int(h)] = data
+    ores = op.migrate(0, n_mig)
+    rc, res = av.avmp_migrate(g.p, 0, n_mig)
+    assert rc == ores.code == av.AVMP_OK
+    assert (res.units_copied, res.recipient_gain, res.bytes_wasted) == \
+        (ores.units_copied, ores.recipient_gain, ores.bytes_wasted)
+    assert res.units_copied > 20                       # live pages did sit in the vacated slots
+    assert av.avmp_stats(g.p) == op.stats()
+    _check_translation(g, op, everything)
+    for h, data in contents.items():
+        assert av.avmp_resolve(g.p, h)[1:] == op.resolve(h)
+        assert np.array_equal(g.read_unit(h), data)
+    assert av.avmp_device_faults(g.p) == (av.AVMP_OK, 0)
+    g.close()
+
+
 @pytest.mark.parametrize("backing", BACKINGS)
 def test_churn_between_steps_keeps_device_table_in_sync(backing):
     """Alloc / free / migrate between decode steps; the device mirror must follow."""
