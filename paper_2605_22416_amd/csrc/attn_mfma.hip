@@ -4,15 +4,15 @@
 //
 // Work split.  For each KV head the (request, page) pairs of the batch, in
 // logical order, form one sequence of pages; it is cut into runs of equal cost
-// (a page costs one, starting a request a few) and wavefront w walks run w,
-// crossing request boundaries as it goes.  A run that covers a whole request
-// writes the output row; otherwise it leaves a partial result (un-normalised
-// sum, running max, running sum) that the merge kernel combines in logical (run)
-// order, one wavefront per (request, KV head).  Every wavefront does about the same
-// work, so the launch has no tail, and the split is a function of the context
-// lengths alone: physical placement and migration cannot change one bit of the
-// result.  One preparation kernel per decode step holds a plan block (page prefix
-// sums, each run's stretch) and, beside it, the blocks that translate every KV
+// (a page costs one, a request at least a few however short it is) and wavefront w
+// walks run w, crossing request boundaries as it goes.  A run that covers a whole
+// request writes the output row; otherwise it leaves a partial result
+// (un-normalised sum, running max, running sum) that the merge kernel combines in
+// logical (run) order, one workgroup per (request, KV head).  Every wavefront does
+// about the same work, and the split is a function of the context lengths alone:
+// physical placement and migration cannot change one bit of the result.  One
+// preparation kernel per decode step holds a plan block (prefix sums of pages and
+// costs, each run's stretch) and, beside it, the blocks that translate every KV
 // handle of every attention layer to its slot.
 //
 // Why the merge is a launch of its own.  Letting the wavefront that completes a
