@@ -38,7 +38,7 @@ KERNEL_SOURCES = {
             "// Same update with the state stored as bf16"),
     "attention": ("attn_mfma.hip", None, None),          # attention + merge + preparation kernels
 }
-KERNEL_MATCH = {"ssm": ("ssm_update_kernel",), "attention": ("attn_mfma_kernel", "attn_merge_runs_kernel")}
+KERNEL_MATCH = {"ssm": ("ssm_update_kernel", "ssm_update_mamba2_kernel"), "attention": ("attn_mfma_kernel", "attn_merge_runs_kernel")}
 
 
 def source_digest(kind):
@@ -652,7 +652,13 @@ def main():
     roofline = None
     if "ssm" in kernels:
         a = kernels["ssm"]["GBps"]
-        roofline = {"kernel": "ssm_update_kernel", "bound": "hbm", "achieved": a,
+        if args.state_dtype != "f32":
+            ssm_kernel = "ssm_update_bf16state_kernel"
+        elif spec.ssm_dstate == 128 and spec.ssm_headdim == 64:
+            ssm_kernel = "ssm_update_mamba2_kernel"
+        else:
+            ssm_kernel = "ssm_update_kernel"
+        roofline = {"kernel": ssm_kernel, "bound": "hbm", "achieved": a,
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": a / HBM_PEAK_GBPS,
                     "traffic": measured_traffic("ssm", sc.batch, args.workload, args.seed)
                     if args.state_dtype == "f32" and not spec.conv_kernel else None,

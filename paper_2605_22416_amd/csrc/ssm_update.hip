@@ -122,6 +122,59 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
   }
 }
 
+// The same update at the Mamba-2 head shape, headdim 64 x dstate 128, with everything the shape
+// fixes folded in at compile time: 1024 threads, a row's 128 values in 32 adjacent lanes, rows p
+// and p + 32 per lane, one pass.  What the general kernel computes at run time (row geometry,
+// loop bounds) sits in front of the first state load of every workgroup, and 8192 workgroups
+// per launch pay for it: 86.1 against 87.2 us per layer at the Jamba-shaped batch of 64.
+template <typename E>
+__global__ __launch_bounds__(1024) void ssm_update_mamba2_kernel(SsmLaunch a) {
+  constexpr uint32_t N = 128, Pd = 64, kLanesPerRow = 32, kRowsPerPass = 32;
+  const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+  const uint32_t H = a.heads;
+  const uint32_t col = tid & (kLanesPerRow - 1), row0 = tid / kLanesPerRow;
+  // the step's own inputs are requested before the handle -> table -> block chain is waited for
+  const uint32_t handle = a.handles[r];
+  const float dt = a.dt[size_t(r) * H + h];
+  const float Ah = a.A[h];
+  const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
+  const float4 Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
+  const uint64_t off = translate_offset(a.P, handle, 1);
+  float* yrow = a.y + (size_t(r) * H + h) * Pd;
+  if (off == ~0ull) {
+    if (tid == 0) count_fault(a.P);
+    if (tid < Pd) yrow[tid] = 0.f;
+    return;
+  }
+  float* tile = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N;
+  const __amdgpu_buffer_rsrc_t rsrc = tile_descriptor(tile, Pd * N * 4);
+  const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
+  float4 s[2];
+  float xs[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const uint32_t p = row0 + k * kRowsPerPass;
+    s[k] = as_float4(load_tile(rsrc, (p * N + 4 * col) * 4));
+    xs[k] = load_elem<E>(xrow + p);
+  }
+  const float decay = expf(dt * Ah);
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const uint32_t p = row0 + k * kRowsPerPass;
+    const float dtx = dt * xs[k];
+    float4 v = s[k];
+    v.x = decay * v.x + dtx * Bv.x;
+    v.y = decay * v.y + dtx * Bv.y;
+    v.z = decay * v.z + dtx * Bv.z;
+    v.w = decay * v.w + dtx * Bv.w;
+    store_tile(rsrc, (p * N + 4 * col) * 4, as_words(v));
+    float part = v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w;
+#pragma unroll
+    for (uint32_t o = kLanesPerRow / 2; o; o >>= 1) part += __shfl_xor(part, int(o));
+    if (col == 0) yrow[p] = part;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Same update with the state stored as bf16 (half the state traffic).  A lane
 // moves 16 bytes = 8 state elements, so a row's N values sit in N/8 adjacent
@@ -243,6 +296,11 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
       else if (big16) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
       else ssm_update_bf16state_kernel<uint16_t, 256, 2, 0, false><<<grid, dim3(256), 0, s>>>(a);
     }
+    return hipGetLastError();
+  }
+  if (a.dstate == 128 && a.headdim == 64) {
+    if (a.dtype == 0) ssm_update_mamba2_kernel<float><<<grid, dim3(1024), 0, s>>>(a);
+    else ssm_update_mamba2_kernel<uint16_t><<<grid, dim3(1024), 0, s>>>(a);
     return hipGetLastError();
   }
   if (a.dtype == 0) {
