@@ -208,11 +208,12 @@ __device__ __forceinline__ uint32_t bf16_round_bits(float f) {   // round to nea
 // HPB heads share one workgroup (THREADS / HPB threads each), so that a workgroup
 // still moves a 32 KiB burst at the Mamba-2 shape (two heads: 51.5 us per layer at
 // batch 64, against 55.7 us with one head and 54.4 us with four).
-template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1>
+// PS: compile-time headdim (0 = read it from the launch), as NS for dstate.
+template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0>
 __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch a) {
   constexpr uint32_t TPH = THREADS / HPB;            // threads per head
   const uint32_t h = blockIdx.x * HPB + threadIdx.x / TPH, r = blockIdx.y, tid = threadIdx.x % TPH;
-  const uint32_t H = a.heads, Pd = a.headdim;
+  const uint32_t H = a.heads, Pd = PS ? uint32_t(PS) : a.headdim;
   const uint32_t N = NS ? uint32_t(NS) : a.dstate;
   const uint64_t off = translate_offset(a.P, a.handles[r], 1);
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
@@ -284,13 +285,17 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   if (a.state_dtype == 1) {
     const bool big16 = uint64_t(a.headdim) * (a.dstate / 8) >= 1024;
     if (a.dtype == 0) {
-      if (exact128 && a.heads % 2 == 0)
+      if (exact128 && a.heads % 2 == 0 && a.headdim == 64)
+        ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<float, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
       else if (big16) ssm_update_bf16state_kernel<float, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
       else ssm_update_bf16state_kernel<float, 256, 2, 0, false><<<grid, dim3(256), 0, s>>>(a);
     } else {
-      if (exact128 && a.heads % 2 == 0)
+      if (exact128 && a.heads % 2 == 0 && a.headdim == 64)
+        ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
       else if (big16) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
