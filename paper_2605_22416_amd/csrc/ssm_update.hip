@@ -44,6 +44,29 @@ __device__ __forceinline__ u32x4s as_words(float4 v) {
   return w;
 }
 
+// Sums over the lanes of a row without going through LDS: data-parallel-primitive moves inside
+// a row of 16 lanes (quad permutes, then mirrors of 8 and of 16 lanes: after each step every lane
+// holds the sum of a group twice as large), and lane 15 of a row added into the row behind it.
+__device__ __forceinline__ float dpp_add(float v, float moved_from) { return v + moved_from; }
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_moved(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+// every lane of a 16-lane row ends up with the row's sum
+__device__ __forceinline__ float sum_row16(float v) {
+  v += dpp_moved<0xB1>(v);      // quad_perm [1,0,3,2]
+  v += dpp_moved<0x4E>(v);      // quad_perm [2,3,0,1]
+  v += dpp_moved<0x141>(v);     // row_half_mirror
+  v += dpp_moved<0x140>(v);     // row_mirror
+  return v;
+}
+// lanes 16..31 and 48..63 end up with the sum of their 32-lane half of the wavefront
+__device__ __forceinline__ float sum_half32_into_upper_row(float v) {
+  v = sum_row16(v);
+  v += dpp_moved<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+  return v;
+}
+
 template <typename E>
 __device__ __forceinline__ float4 load4(const E* p);
 template <>
@@ -168,10 +191,8 @@ __global__ __launch_bounds__(1024) void ssm_update_mamba2_kernel(SsmLaunch a) {
     v.z = decay * v.z + dtx * Bv.z;
     v.w = decay * v.w + dtx * Bv.w;
     store_tile(rsrc, (p * N + 4 * col) * 4, as_words(v));
-    float part = v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w;
-#pragma unroll
-    for (uint32_t o = kLanesPerRow / 2; o; o >>= 1) part += __shfl_xor(part, int(o));
-    if (col == 0) yrow[p] = part;
+    const float part = sum_half32_into_upper_row(v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w);
+    if (col == kLanesPerRow - 1) yrow[p] = part;
   }
 }
 
@@ -264,9 +285,13 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
         const u32x4s packed = {out[0], out[1], out[2], out[3]};
         store_tile(rsrc, (p * N + 8 * col) * 2, packed);
       }
+      if (NS == 128) {                         // a row is one 16-lane row of the wavefront
+        part = sum_row16(part);
+      } else {
 #pragma unroll
-      for (uint32_t o = 16; o; o >>= 1)
-        if (o < lpr) part += __shfl_xor(part, int(o));
+        for (uint32_t o = 16; o; o >>= 1)
+          if (o < lpr) part += __shfl_xor(part, int(o));
+      }
       if ((EXACT || p < Pd) && col == 0) yrow[p] = part;
     }
   }
