@@ -217,6 +217,7 @@ class Pools:
         self.arena = np.zeros(self.usable, dtype=np.uint8) if with_data else None
         self.unrounded_state = {}      # handle -> float64 state of its last update, before storage
         self.update_scale = {}         # handle -> |a*S| + |dt*x*B| of that update (rounding-noise scale)
+        self.output_scale = {}         # handle -> sum_n |S*C| behind each y of the last step (same use)
         # counters (the 64-bit logical operation counter of the paper + outcome counters)
         self.ops = 0
         self.capacity_errors = 0
@@ -506,6 +507,7 @@ class Pools:
             self.update_scale[int(handles[r])] = np.abs(decayed) + np.abs(driven)
             S = decayed + driven
             y[r] = (S * Cf[r][None, None, :]).sum(axis=2)
+            self.output_scale[int(handles[r])] = (np.abs(S) * np.abs(Cf[r])[None, None, :]).sum(axis=2)
             self.unrounded_state[int(handles[r])] = S      # for tests of the storage rounding
             if sh.state_dtype == "f32":
                 raw.view(np.float32)[:] = S.astype(np.float32).reshape(-1)

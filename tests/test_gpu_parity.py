@@ -20,13 +20,23 @@ def _harness():
     return gpu_harness
 
 
-def _check_outputs(spec, got_o, got_y, ref_o, ref_y, what=""):
+def _check_outputs(spec, got_o, got_y, ref_o, ref_y, what="", y_scale=None, y_tol=None):
+    """Row-wise max-norm relative error of o and y against the tolerance of the element type.
+    y_scale ([n_ssm][batch][H][P], the oracle's sum_n |S*C| behind each y): the error of a row of y
+    is then taken relative to the largest such sum in the row instead of the largest |y|: a sum of
+    products carries rounding noise in proportion to the size of its terms, whatever cancels.
+    y_tol replaces the tolerance for y."""
     tol = TOL[spec.dtype]
+    y_tol = tol if y_tol is None else y_tol
     assert np.isfinite(got_o).all() and np.isfinite(got_y).all(), what + ": non-finite output"
     eo = helpers.rel_err_rows(got_o, ref_o)
-    ey = helpers.rel_err_rows(got_y, ref_y)
+    if y_scale is None:
+        ey = helpers.rel_err_rows(got_y, ref_y)
+    else:
+        num = np.abs(np.asarray(got_y, dtype=np.float64) - ref_y).max(axis=-1)
+        ey = num / np.maximum(np.asarray(y_scale).max(axis=-1), 1e-30)
     assert eo.size == 0 or eo.max() <= tol, "%s: attention rel err %.3g > %g" % (what, eo.max(), tol)
-    assert ey.size == 0 or ey.max() <= tol, "%s: ssm y rel err %.3g > %g" % (what, ey.max(), tol)
+    assert ey.size == 0 or ey.max() <= y_tol, "%s: ssm y rel err %.3g > %g" % (what, ey.max(), y_tol)
     return float(eo.max()) if eo.size else 0.0, float(ey.max()) if ey.size else 0.0
 
 

@@ -1,7 +1,13 @@
 """GPU parity on seeded random shapes: model shape, layer pattern, batch, contexts
 (zero and ragged included), placement, state storage type and convolution window
 are all drawn per seed; two decode steps each, the second one with a migration in
-between, against the CPU oracle.  Tolerances as in test_gpu_parity.py."""
+between, against the CPU oracle.  Tolerances as in test_gpu_parity.py, with two
+things the drawn shapes need: a row of y is measured against the size of the
+terms that were summed into it (the oracle's sum_n |S*C|; rows of one element and
+unscaled inputs cancel freely, and fp32 rounding noise goes with the terms, not
+with what is left of them), and with the state stored as bf16 the second step is
+held to one bf16 ulp, 2^-7: it starts from stored codes that may differ from the
+oracle's by one where the exact value sat on a rounding boundary."""
 import numpy as np
 import pytest
 
@@ -40,7 +46,7 @@ def _draw(seed):
     return spec, ctx, rng, refused
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(120))
 def test_random_shape(seed):
     from paper_2605_22416_amd import binding as av
     spec, ctx, rng, refused = _draw(seed)
@@ -80,7 +86,9 @@ def test_random_shape(seed):
         ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, inp["x"], inp["dt"],
                                       inp["A"], inp["B"], inp["C"], **extra)
         o, y = g.step(inp, conv=conv)
-        _check_outputs(spec, o, y, ref_o, ref_y, what + " step %d" % step)
+        y_scale = np.stack([np.stack([op.output_scale[int(h)] for h in ssm[ls]]) for ls in range(spec.n_ssm)])
+        _check_outputs(spec, o, y, ref_o, ref_y, what + " step %d" % step, y_scale=y_scale,
+                       y_tol=2.0 ** -7 if spec.state_dtype == "bf16" and step > 0 else None)
     if spec.state_dtype == "f32":
         _check_states(spec, g, op, ssm, what)
     if spec.conv_kernel:
