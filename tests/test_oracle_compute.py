@@ -185,11 +185,17 @@ def test_ssm_step_bruteforce_scalar_loops():
             a = math.exp(float(inp["dt"][0][r, h]) * float(inp["A"][0][h]))
             for pp in range(3):
                 acc = 0.0
+                size = 0.0
                 for n in range(4):
                     s = a * float(S0[r][h, pp, n]) + float(inp["dt"][0][r, h]) * x[r, h, pp] * B[r, n]
                     assert S1[h, pp, n] == np.float32(s)
                     acc += s * C[r, n]
+                    size += abs(s * C[r, n])
                 assert abs(y[r, h, pp] - acc) < 1e-14
+                # the size of the terms behind y, which GPU tests measure rounding noise against:
+                # never less than |y|, and exactly the sum of the absolute products
+                scale = p.output_scale[int(ssm[0, r])][h, pp]
+                assert abs(scale - size) < 1e-14 and scale >= abs(y[r, h, pp]) - 1e-14
 
 
 def test_ssm_special_cases():
