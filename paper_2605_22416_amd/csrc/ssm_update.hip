@@ -146,13 +146,18 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
 }
 
 // The same update at the Mamba-2 head shape, headdim 64 x dstate 128, with everything the shape
-// fixes folded in at compile time: 1024 threads, a row's 128 values in 32 adjacent lanes, rows p
-// and p + 32 per lane, one pass.  What the general kernel computes at run time (row geometry,
-// loop bounds) sits in front of the first state load of every workgroup, and 8192 workgroups
-// per launch pay for it: 86.1 against 87.2 us per layer at the Jamba-shaped batch of 64.
+// fixes folded in at compile time: a row's 128 values in 32 adjacent lanes, 512 threads that take
+// rows p, p + 16, p + 32 and p + 48 each, one pass.  What the general kernel computes at run time
+// (row geometry, loop bounds) sits in front of the first state load of every workgroup, and 8192
+// workgroups per launch pay for it: 86.1 against 87.2 us per layer at the Jamba-shaped batch of
+// 64 with 1024 threads and two rows per lane.  With that out of the way four workgroups of 512
+// threads per compute unit do better than two of 1024 (the step: 2573 against 2588 us; 256
+// threads and eight rows per lane: 2607 us).
+constexpr int kMamba2Threads = 512;
 template <typename E>
-__global__ __launch_bounds__(1024) void ssm_update_mamba2_kernel(SsmLaunch a) {
-  constexpr uint32_t N = 128, Pd = 64, kLanesPerRow = 32, kRowsPerPass = 32;
+__global__ __launch_bounds__(kMamba2Threads) void ssm_update_mamba2_kernel(SsmLaunch a) {
+  constexpr uint32_t N = 128, Pd = 64, kLanesPerRow = 32, kRowsPerPass = kMamba2Threads / kLanesPerRow;
+  constexpr int kRows = Pd / kRowsPerPass;
   const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
   const uint32_t H = a.heads;
   const uint32_t col = tid & (kLanesPerRow - 1), row0 = tid / kLanesPerRow;
@@ -172,17 +177,17 @@ __global__ __launch_bounds__(1024) void ssm_update_mamba2_kernel(SsmLaunch a) {
   float* tile = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N;
   const __amdgpu_buffer_rsrc_t rsrc = tile_descriptor(tile, Pd * N * 4);
   const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
-  float4 s[2];
-  float xs[2];
+  float4 s[kRows];
+  float xs[kRows];
 #pragma unroll
-  for (int k = 0; k < 2; ++k) {
+  for (int k = 0; k < kRows; ++k) {
     const uint32_t p = row0 + k * kRowsPerPass;
     s[k] = as_float4(load_tile(rsrc, (p * N + 4 * col) * 4));
     xs[k] = load_elem<E>(xrow + p);
   }
   const float decay = expf(dt * Ah);
 #pragma unroll
-  for (int k = 0; k < 2; ++k) {
+  for (int k = 0; k < kRows; ++k) {
     const uint32_t p = row0 + k * kRowsPerPass;
     const float dtx = dt * xs[k];
     float4 v = s[k];
@@ -227,8 +232,12 @@ __device__ __forceinline__ uint32_t bf16_round_bits(float f) {   // round to nea
 }
 
 // HPB heads share one workgroup (THREADS / HPB threads each), so that a workgroup
-// still moves a 32 KiB burst at the Mamba-2 shape (two heads: 51.5 us per layer at
-// batch 64, against 55.7 us with one head and 54.4 us with four).
+// still moves a 32 KiB burst (two heads of 1024 threads together: 51.5 us per layer at
+// batch 64, against 55.7 us with one head and 54.4 us with four, all with the row geometry
+// worked out at run time).  With headdim and dstate compile-time constants a head per
+// workgroup of 512 threads is the fastest shape at headdim 64 x dstate 128 (the step with a
+// bf16 state: 1560 us against 1569 us for two heads in 1024 threads, 1595 us for two heads in
+// 512 threads with four rows per lane, 1598 us for 256 threads).
 // PS: compile-time headdim (0 = read it from the launch), as NS for dstate.
 template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0>
 __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch a) {
@@ -310,16 +319,16 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   if (a.state_dtype == 1) {
     const bool big16 = uint64_t(a.headdim) * (a.dstate / 8) >= 1024;
     if (a.dtype == 0) {
-      if (exact128 && a.heads % 2 == 0 && a.headdim == 64)
-        ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      if (exact128 && a.headdim == 64)     // the Mamba-2 shape: a head per workgroup of 512 threads, all compile-time
+        ssm_update_bf16state_kernel<float, 512, 2, 128, true, 1, 64><<<grid, dim3(512), 0, s>>>(a);
       else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<float, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
       else if (big16) ssm_update_bf16state_kernel<float, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
       else ssm_update_bf16state_kernel<float, 256, 2, 0, false><<<grid, dim3(256), 0, s>>>(a);
     } else {
-      if (exact128 && a.heads % 2 == 0 && a.headdim == 64)
-        ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      if (exact128 && a.headdim == 64)
+        ssm_update_bf16state_kernel<uint16_t, 512, 2, 128, true, 1, 64><<<grid, dim3(512), 0, s>>>(a);
       else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
@@ -329,8 +338,8 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
     return hipGetLastError();
   }
   if (a.dstate == 128 && a.headdim == 64) {
-    if (a.dtype == 0) ssm_update_mamba2_kernel<float><<<grid, dim3(1024), 0, s>>>(a);
-    else ssm_update_mamba2_kernel<uint16_t><<<grid, dim3(1024), 0, s>>>(a);
+    if (a.dtype == 0) ssm_update_mamba2_kernel<float><<<grid, dim3(kMamba2Threads), 0, s>>>(a);
+    else ssm_update_mamba2_kernel<uint16_t><<<grid, dim3(kMamba2Threads), 0, s>>>(a);
     return hipGetLastError();
   }
   if (a.dtype == 0) {
