@@ -146,17 +146,28 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
 }
 
 // The same update at the Mamba-2 head shape, headdim 64 x dstate 128, with everything the shape
-// fixes folded in at compile time: a row's 128 values in 32 adjacent lanes, 512 threads that take
-// rows p, p + 16, p + 32 and p + 48 each, one pass.  What the general kernel computes at run time
-// (row geometry, loop bounds) sits in front of the first state load of every workgroup, and 8192
-// workgroups per launch pay for it: 86.1 against 87.2 us per layer at the Jamba-shaped batch of
-// 64 with 1024 threads and two rows per lane.  With that out of the way four workgroups of 512
-// threads per compute unit do better than two of 1024 (the step: 2573 against 2588 us; 256
-// threads and eight rows per lane: 2607 us).
-constexpr int kMamba2Threads = 512;
-template <typename E>
-__global__ __launch_bounds__(kMamba2Threads) void ssm_update_mamba2_kernel(SsmLaunch a) {
-  constexpr uint32_t N = 128, Pd = 64, kLanesPerRow = 32, kRowsPerPass = kMamba2Threads / kLanesPerRow;
+// fixes folded in at compile time: a row's 128 values in 32 adjacent lanes, THREADS / 32 rows per
+// pass, one pass.  What the general kernel computes at run time (row geometry, loop bounds) sits
+// in front of the first state load of every workgroup, and 8192 workgroups per launch pay for
+// it: 86.1 against 87.2 us per layer at the Jamba-shaped batch of 64 with 1024 threads.
+//
+// Two shapes of it are used, by the length of the launch (measured on the decode step at
+// batches of 32 ... 512 requests of 128 heads; us per layer):
+//   * 512 threads, four rows per lane, state asked for as early as possible and the arithmetic
+//     on B, C and the decay done while the loads are in flight: quickest to start and to drain,
+//     sustains 6.2 - 6.4 TB/s however long the launch (45.4 / 85.8 / 127.8 / 170.2 / 257.1 /
+//     714.0 at batch 32 / 64 / 96 / 128 / 192 / 512);
+//   * 1024 threads, two rows per lane, that arithmetic finished BEFORE the state is asked for,
+//     so that a row is stored the moment it arrives: slower off the mark, but 6.4 - 6.7 TB/s
+//     once the launch is long enough (46.1 / 86.2 / 127.3 / 168.5 / 247.0 / 649.0; the general
+//     kernel, which orders its work the same way, 87.1 / 128.9 / 171.2 / 248.0 / 652.6 from
+//     batch 64 on).  With 512 threads this order is the slowest of all (87.0 at batch 64).
+// The step is 2574 us at batch 64 with the first shape, 2581 us with the second.
+constexpr uint64_t kShortLaunchTiles = 80 * 128;        // fp32 state: below this many (head, request) tiles, 512 threads
+constexpr uint64_t kSmallLaunchTiles16 = 96 * 128;      // bf16 state (measured crossover between 64 and 128 requests)
+template <typename E, int THREADS, bool ARITHMETIC_FIRST>
+__global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a) {
+  constexpr uint32_t N = 128, Pd = 64, kLanesPerRow = 32, kRowsPerPass = THREADS / kLanesPerRow;
   constexpr int kRows = Pd / kRowsPerPass;
   const uint32_t h = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
   const uint32_t H = a.heads;
@@ -177,6 +188,14 @@ __global__ __launch_bounds__(kMamba2Threads) void ssm_update_mamba2_kernel(SsmLa
   float* tile = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N;
   const __amdgpu_buffer_rsrc_t rsrc = tile_descriptor(tile, Pd * N * 4);
   const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
+  float decay = 0.f;
+  if (ARITHMETIC_FIRST) {
+    // nothing below may move above this point: B, C and the decay are in registers before the
+    // first state load goes out
+    decay = expf(dt * Ah);
+    asm volatile("" :: "v"(decay), "v"(Bv.x), "v"(Bv.y), "v"(Bv.z), "v"(Bv.w), "v"(Cv.x), "v"(Cv.y),
+                 "v"(Cv.z), "v"(Cv.w) : "memory");
+  }
   float4 s[kRows];
   float xs[kRows];
 #pragma unroll
@@ -185,7 +204,7 @@ __global__ __launch_bounds__(kMamba2Threads) void ssm_update_mamba2_kernel(SsmLa
     s[k] = as_float4(load_tile(rsrc, (p * N + 4 * col) * 4));
     xs[k] = load_elem<E>(xrow + p);
   }
-  const float decay = expf(dt * Ah);
+  if (!ARITHMETIC_FIRST) decay = expf(dt * Ah);
 #pragma unroll
   for (int k = 0; k < kRows; ++k) {
     const uint32_t p = row0 + k * kRowsPerPass;
@@ -235,9 +254,10 @@ __device__ __forceinline__ uint32_t bf16_round_bits(float f) {   // round to nea
 // still moves a 32 KiB burst (two heads of 1024 threads together: 51.5 us per layer at
 // batch 64, against 55.7 us with one head and 54.4 us with four, all with the row geometry
 // worked out at run time).  With headdim and dstate compile-time constants a head per
-// workgroup of 512 threads is the fastest shape at headdim 64 x dstate 128 (the step with a
-// bf16 state: 1560 us against 1569 us for two heads in 1024 threads, 1595 us for two heads in
-// 512 threads with four rows per lane, 1598 us for 256 threads).
+// workgroup of 512 threads is the fastest shape at headdim 64 x dstate 128 for launches of up
+// to about 96 requests (the step with a bf16 state at batch 64: 1560 us against 1569 us for two
+// heads in 1024 threads, 1595 us for two heads in 512 threads with four rows per lane, 1598 us
+// for 256 threads; at batch 128 / 256: 3036 / 5920 against 3010 / 5742 us).
 // PS: compile-time headdim (0 = read it from the launch), as NS for dstate.
 template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0>
 __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch a) {
@@ -318,17 +338,22 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   const bool exact128 = a.dstate == 128 && a.headdim % 64 == 0;
   if (a.state_dtype == 1) {
     const bool big16 = uint64_t(a.headdim) * (a.dstate / 8) >= 1024;
+    const bool small16 = uint64_t(a.heads) * a.batch < kSmallLaunchTiles16;
     if (a.dtype == 0) {
-      if (exact128 && a.headdim == 64)     // the Mamba-2 shape: a head per workgroup of 512 threads, all compile-time
+      if (exact128 && a.headdim == 64 && small16)     // the Mamba-2 shape: a head per workgroup of 512 threads
         ssm_update_bf16state_kernel<float, 512, 2, 128, true, 1, 64><<<grid, dim3(512), 0, s>>>(a);
+      else if (exact128 && a.headdim == 64 && a.heads % 2 == 0)
+        ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<float, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
       else if (big16) ssm_update_bf16state_kernel<float, 1024, 1, 0, false><<<grid, dim3(1024), 0, s>>>(a);
       else ssm_update_bf16state_kernel<float, 256, 2, 0, false><<<grid, dim3(256), 0, s>>>(a);
     } else {
-      if (exact128 && a.headdim == 64)
+      if (exact128 && a.headdim == 64 && small16)
         ssm_update_bf16state_kernel<uint16_t, 512, 2, 128, true, 1, 64><<<grid, dim3(512), 0, s>>>(a);
+      else if (exact128 && a.headdim == 64 && a.heads % 2 == 0)
+        ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
@@ -338,8 +363,14 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
     return hipGetLastError();
   }
   if (a.dstate == 128 && a.headdim == 64) {
-    if (a.dtype == 0) ssm_update_mamba2_kernel<float><<<grid, dim3(kMamba2Threads), 0, s>>>(a);
-    else ssm_update_mamba2_kernel<uint16_t><<<grid, dim3(kMamba2Threads), 0, s>>>(a);
+    const bool short_launch = uint64_t(a.heads) * a.batch < kShortLaunchTiles;
+    if (a.dtype == 0) {
+      if (short_launch) ssm_update_mamba2_kernel<float, 512, false><<<grid, dim3(512), 0, s>>>(a);
+      else ssm_update_mamba2_kernel<float, 1024, true><<<grid, dim3(1024), 0, s>>>(a);
+    } else {
+      if (short_launch) ssm_update_mamba2_kernel<uint16_t, 512, false><<<grid, dim3(512), 0, s>>>(a);
+      else ssm_update_mamba2_kernel<uint16_t, 1024, true><<<grid, dim3(1024), 0, s>>>(a);
+    }
     return hipGetLastError();
   }
   if (a.dtype == 0) {
