@@ -126,6 +126,8 @@ struct avmp_vmm_arena {
   avmp::VmmArena impl;
 };
 
+constexpr uint32_t kMaxBatch = 65535;        // requests of one decode step (a grid dimension)
+
 struct avmp_pools {
   avmp_config_t cfg{};
   avmp::PoolState st;
@@ -133,6 +135,8 @@ struct avmp_pools {
   int device = -1;                     // the GPU the arena lives on
   uint8_t* arena = nullptr;
   uint32_t* table_dev = nullptr;
+  uint32_t* conv_arrivals_dev = nullptr;       // per request of a batch, zero between launches; only where
+                                               // the recurrence kernel runs the convolution itself
   unsigned long long* faults_dev = nullptr;
   unsigned long long* faults_host = nullptr;   // pinned: where avmp_device_faults reads the counter to
   float* ws = nullptr;                 // work buffer of the decode step (see WorkLayout)
@@ -375,7 +379,7 @@ int check_step(avmp_pools* p, const avmp_step_t* st, uint32_t* n_attn_out, uint3
     else if (st->layer_kind[i] == AVMP_LAYER_SSM) ++n_ssm;
     else return fail(AVMP_ERR_INVALID_ARG, "unknown layer kind");
   }
-  if (st->batch > 65535) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
+  if (st->batch > kMaxBatch) return fail(AVMP_ERR_INVALID_ARG, "batch above 65535");
   if (n_attn && uint64_t(st->batch) * st->max_pages > 0x7FFFFFFFull)      // page counts are summed in 32 bits
     return fail(AVMP_ERR_INVALID_ARG, "batch x max_pages above 2^31 - 1");
   if (n_attn && st->batch &&
@@ -487,7 +491,15 @@ int run_step(avmp_pools* p, const avmp_step_t* st, hipStream_t s, uint32_t n_att
       a.dstate = c.ssm_dstate;
       a.dtype = c.dtype;
       a.state_dtype = c.ssm_state_dtype;
-      if (conv) {
+      if (conv && p->conv_arrivals_dev != nullptr &&
+          avmp::ssm_fuses_conv(c.ssm_conv_kernel, c.ssm_heads, c.ssm_headdim, c.ssm_dstate, c.ssm_state_dtype, st->batch)) {
+        // the recurrence kernel runs the convolution itself
+        a.conv_u = static_cast<const char*>(st->xbc) + size_t(is) * st->batch * conv_dim * eb;
+        a.conv_taps = static_cast<const char*>(st->conv_taps) + size_t(is) * c.ssm_conv_kernel * conv_dim * eb;
+        a.conv_bias = static_cast<const char*>(st->conv_bias) + size_t(is) * conv_dim * eb;
+        a.conv_arrivals = p->conv_arrivals_dev;
+        a.conv_k = c.ssm_conv_kernel;
+      } else if (conv) {
         // x, B and C of this layer come out of the convolution, as fp32
         avmp::ConvLaunch cv{};
         cv.P = P;
@@ -591,8 +603,14 @@ int avmp_pools_create(const avmp_config_t* cfg, void* arena_dev, size_t arena_by
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->faults_dev), sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(p->faults_dev, 0, sizeof(unsigned long long));
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&p->faults_host), sizeof(unsigned long long), hipHostMallocDefault);
+    if (e == hipSuccess && avmp::ssm_may_fuse_conv(cfg->ssm_conv_kernel, cfg->ssm_heads, cfg->ssm_headdim, cfg->ssm_dstate)) {
+      const size_t bytes = size_t(kMaxBatch) * avmp::kArrivalStride * sizeof(uint32_t);
+      e = hipMalloc(reinterpret_cast<void**>(&p->conv_arrivals_dev), bytes);
+      if (e == hipSuccess) e = hipMemset(p->conv_arrivals_dev, 0, bytes);
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
+      if (p->conv_arrivals_dev) (void)hipFree(p->conv_arrivals_dev);
       if (p->table_dev) (void)hipFree(p->table_dev);
       if (p->faults_dev) (void)hipFree(p->faults_dev);
       if (p->faults_host) (void)hipHostFree(p->faults_host);
@@ -618,6 +636,7 @@ int avmp_pools_destroy(avmp_pools_t* p) {
     if (p->ws) (void)hipFree(p->ws);
     for (void* old : p->ws_retired) (void)hipFree(old);
     (void)hipFree(p->table_dev);
+    if (p->conv_arrivals_dev) (void)hipFree(p->conv_arrivals_dev);
     (void)hipFree(p->faults_dev);
     (void)hipHostFree(p->faults_host);
   }

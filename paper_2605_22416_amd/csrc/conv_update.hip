@@ -8,36 +8,12 @@
 // channels of one request and is the only one to touch their window, so the
 // update in place needs no ordering.  Outputs are fp32, split into the x, B and C
 // arrays the recurrence kernel reads.
+#include "conv_window.hpp"
 #include "kernels.hpp"
 
 namespace avmp {
 
 namespace {
-
-template <typename E>
-struct Vec;
-template <>
-struct Vec<float> {
-  static constexpr int N = 4;
-  float4 raw;
-  __device__ float get(int i) const { return reinterpret_cast<const float*>(&raw)[i]; }
-};
-template <>
-struct Vec<uint16_t> {
-  static constexpr int N = 8;
-  uint4 raw;
-  __device__ float get(int i) const {
-    const uint32_t w = reinterpret_cast<const uint32_t*>(&raw)[i >> 1];
-    return (i & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-  }
-};
-
-template <typename E>
-__device__ __forceinline__ Vec<E> load_vec(const void* p) {
-  Vec<E> v;
-  v.raw = *static_cast<const decltype(v.raw)*>(p);
-  return v;
-}
 
 template <typename E, int K>
 __global__ __launch_bounds__(256) void conv_update_kernel(ConvLaunch a) {
@@ -45,31 +21,19 @@ __global__ __launch_bounds__(256) void conv_update_kernel(ConvLaunch a) {
   const uint32_t r = blockIdx.y;
   const uint32_t c0 = (blockIdx.x * 256u + threadIdx.x) * V;
   if (c0 >= a.conv_dim) return;
+  const size_t row = size_t(a.conv_dim) * sizeof(E);
+  ConvInputs<E, K> cv;
+  cv.load_token(static_cast<const uint8_t*>(a.u) + (size_t(r) * a.conv_dim + c0) * sizeof(E),
+                static_cast<const uint8_t*>(a.taps) + size_t(c0) * sizeof(E),
+                static_cast<const uint8_t*>(a.bias) + size_t(c0) * sizeof(E), row);
   // a handle that does not translate is counted by the recurrence kernel, which skips the request
   const uint64_t off = translate_offset(a.P, a.handles[r], 1);
   if (off == ~0ull) return;
-  const size_t row = size_t(a.conv_dim) * sizeof(E);
   uint8_t* win = a.P.arena + off + a.state_bytes + size_t(c0) * sizeof(E);
-  Vec<E> in[K];
-#pragma unroll
-  for (int k = 0; k < K - 1; ++k) in[k] = load_vec<E>(win + k * row);
-  in[K - 1] = load_vec<E>(static_cast<const uint8_t*>(a.u) + (size_t(r) * a.conv_dim + c0) * sizeof(E));
-  Vec<E> w[K];
-#pragma unroll
-  for (int k = 0; k < K; ++k)
-    w[k] = load_vec<E>(static_cast<const uint8_t*>(a.taps) + (size_t(k) * a.conv_dim + c0) * sizeof(E));
-  const Vec<E> b = load_vec<E>(static_cast<const uint8_t*>(a.bias) + size_t(c0) * sizeof(E));
+  cv.load_window(win, row);
   float out[V];
-#pragma unroll
-  for (int i = 0; i < V; ++i) {
-    float v = b.get(i);
-#pragma unroll
-    for (int k = 0; k < K; ++k) v = fmaf(w[k].get(i), in[k].get(i), v);
-    out[i] = v / (1.f + expf(-v));
-  }
-  // the window moves on: row k takes row k+1, the last row takes the new token
-#pragma unroll
-  for (int k = 0; k < K - 1; ++k) *reinterpret_cast<decltype(in[0].raw)*>(win + k * row) = in[k + 1].raw;
+  cv.outputs(out);
+  cv.advance(win, row);
   // channels [0, HP) are x, then N of B, then N of C; a lane's channels never straddle two of them
   const uint32_t hp = a.heads * a.headdim;
   float* dst;

@@ -46,6 +46,14 @@ struct SsmLaunch {
   uint32_t batch, heads, headdim, dstate;
   uint32_t dtype;            // x, B, C element type: 0 f32, 1 bf16
   uint32_t state_dtype;      // storage type of the state block: 0 f32, 1 bf16
+  // Convolution done by the recurrence kernel itself (conv_k != 0; see ssm_fuses_conv): x, B and
+  // C above are not read, they come out of the block's window and these; dtype is their type.
+  const void* conv_u;        // device [batch][H*P + 2*N] elements: this token's inputs
+  const void* conv_taps;     // device [K][H*P + 2*N] elements
+  const void* conv_bias;     // device [H*P + 2*N] elements
+  uint32_t* conv_arrivals;   // device [batch][kArrivalStride], zero between launches: workgroups of a request that
+                             // have read its window
+  uint32_t conv_k;           // taps, 0: no convolution
 };
 
 struct ConvLaunch {
@@ -106,6 +114,20 @@ hipError_t launch_attention_prepare(const AttnLaunch& a, const uint32_t* handles
 hipError_t launch_attention_mfma(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge_runs(const AttnLaunch& a, hipStream_t s);
 hipError_t launch_attention_merge(const AttnLaunch& a, hipStream_t s);
+// Arrival counters sit a cache line apart: additions to one line are carried out one after the
+// other, whichever word they go to (counters of 64 requests packed into two lines: 110 us per layer
+// against 86 us without the convolution).
+constexpr uint32_t kArrivalStride = 32;
+
+// Whether the recurrence kernel runs the layer's convolution itself, so that no convolution
+// launch is needed: at the Mamba-2 head shape (headdim 64 x dstate 128) with four taps, for
+// every launch with a bf16 state and for the shorter launches with an fp32 state (measured, us
+// per layer, convolution + recurrence as two launches against one: fp32 state 7.9 + 90.2
+// against 92.5 at 64 requests of 128 heads, 15.2 + 333.7 against 361.8 at 256; bf16 state
+// 8.0 + 49.8 against 52.3 and 15.1 + 190.7 against 191.9).  ssm_may_fuse_conv: for some batch.
+bool ssm_may_fuse_conv(uint32_t taps_k, uint32_t heads, uint32_t headdim, uint32_t dstate);
+bool ssm_fuses_conv(uint32_t taps_k, uint32_t heads, uint32_t headdim, uint32_t dstate,
+                    uint32_t state_dtype, uint32_t batch);
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s);
 hipError_t launch_table_updates(uint32_t* table, const TableUpdate* upd, uint32_t n, hipStream_t s);
 hipError_t launch_zero_units(const DevPools& P, int pool, const uint32_t* slots, uint32_t n,

@@ -1,6 +1,7 @@
 // In-place SSM single-token state update for gfx950 (Background, "KV Cache and
 // SSM State Management": one contiguous block per layer per sequence, updated in
 // place with contiguous reads and writes).
+#include "conv_window.hpp"
 #include "kernels.hpp"
 
 #include <cmath>
@@ -47,7 +48,6 @@ __device__ __forceinline__ u32x4s as_words(float4 v) {
 // Sums over the lanes of a row without going through LDS: data-parallel-primitive moves inside
 // a row of 16 lanes (quad permutes, then mirrors of 8 and of 16 lanes: after each step every lane
 // holds the sum of a group twice as large), and lane 15 of a row added into the row behind it.
-__device__ __forceinline__ float dpp_add(float v, float moved_from) { return v + moved_from; }
 template <int CTRL, int ROW_MASK = 0xF>
 __device__ __forceinline__ float dpp_moved(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
@@ -145,6 +145,129 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// The layer's short convolution done by the recurrence workgroup itself, at the Mamba-2 head
+// shape: a launch of its own costs about 8 us per layer for 1.7 MB of traffic, most of it the
+// launch.  A workgroup needs the convolution's outputs for the 2 x 128 channels of B and C,
+// which every workgroup of the request needs, and for the x channels of its own head(s) (XCH
+// of them, touched by nobody else).  Thread t < 256 takes channel t of [B | C], the XCH threads
+// behind them one x channel each; outputs go through LDS to the lanes that use them.  (Sixteen
+// bytes of channels per lane, as in the stand-alone kernel, leave the whole workgroup waiting at
+// its barrier for two wavefronts that compute eight channels each: 93.8 us per layer against
+// 86.0 us without the convolution.)  The x rows of the window move on at once.  The B and C rows
+// are read by every workgroup of the request, so they move on only after all of them have
+// read: behind the barrier, which every read of the workgroup has passed, the workgroup
+// takes a ticket from the request's arrival counter, and the one that draws the last ticket
+// reads the rows again at the end of the kernel, writes them one place on and clears the
+// counter.  No workgroup waits for another.
+// ---------------------------------------------------------------------------
+// An element as loaded, one to a register (16-bit elements held two to a register would be
+// packed the moment they arrive, and the loads behind them would wait for that).
+template <typename E>
+struct Held;
+template <>
+struct Held<float> {
+  static __device__ __forceinline__ uint32_t load(const float* p) { return __float_as_uint(*p); }
+  static __device__ __forceinline__ void store(float* p, uint32_t bits) { *p = __uint_as_float(bits); }
+  static __device__ __forceinline__ float value(uint32_t bits) { return __uint_as_float(bits); }
+};
+template <>
+struct Held<uint16_t> {
+  static __device__ __forceinline__ uint32_t load(const uint16_t* p) { return *p; }
+  static __device__ __forceinline__ void store(uint16_t* p, uint32_t bits) { *p = uint16_t(bits); }
+  static __device__ __forceinline__ float value(uint32_t bits) { return bf16_bits_to_float(bits); }
+};
+
+template <typename E, int K, int XCH>
+struct FusedConv {
+  static constexpr int V = Vec<E>::N;
+  static constexpr uint32_t kPd = 64, kN = 128, kShared = 2 * kN;
+  static constexpr int kStaged = int(kShared) + XCH;     // floats of LDS: B, C, x of the workgroup's heads
+  uint32_t in[K], taps[K], bias;   // as stored (Held); in[K-1] is the new token
+  E* win;                   // this thread's channel in row 0 of the window
+  uint32_t conv_dim, channel, ticket;
+  bool mine;                // the thread has a channel
+
+  // asks for the new token's input, the taps and the bias: nothing here waits for the handle
+  __device__ __forceinline__ void request_token(const SsmLaunch& a, uint32_t r, uint32_t first_head) {
+    const uint32_t t = threadIdx.x, hp = a.heads * kPd;
+    conv_dim = hp + kShared;
+    mine = t < kShared + uint32_t(XCH);
+    channel = t < kShared ? hp + t : first_head * kPd + (t - kShared);
+    ticket = 0;
+    if (mine) {
+#pragma unroll
+      for (int k = 0; k < K; ++k)
+        taps[k] = Held<E>::load(static_cast<const E*>(a.conv_taps) + size_t(k) * conv_dim + channel);
+      bias = Held<E>::load(static_cast<const E*>(a.conv_bias) + channel);
+      in[K - 1] = Held<E>::load(static_cast<const E*>(a.conv_u) + size_t(r) * conv_dim + channel);
+    }
+  }
+  // asks for the channel's window rows behind the block's state
+  __device__ __forceinline__ void request_window(uint8_t* block, uint64_t state_bytes) {
+    win = reinterpret_cast<E*>(block + state_bytes) + channel;
+    if (mine) {
+#pragma unroll
+      for (int k = 0; k < K - 1; ++k) in[k] = Held<E>::load(win + size_t(k) * conv_dim);
+    }
+  }
+  // the channel's output to LDS, the workgroup's own rows moved on; the caller's barrier follows
+  __device__ __forceinline__ void finish(float* staged) {
+    if (!mine) return;
+    // what was asked for above is first looked at here (widening a value where it was loaded
+    // would wait for it there, in front of the state loads)
+#pragma unroll
+    for (int k = 0; k < K; ++k) asm volatile("" : "+v"(in[k]), "+v"(taps[k]));
+    asm volatile("" : "+v"(bias));
+    float x[K], w[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      x[k] = Held<E>::value(in[k]);
+      w[k] = Held<E>::value(taps[k]);
+    }
+    staged[threadIdx.x] = conv_channel<K>(Held<E>::value(bias), w, x);
+    if (threadIdx.x >= kShared) {
+#pragma unroll
+      for (int k = 0; k < K - 1; ++k) Held<E>::store(win + size_t(k) * conv_dim, in[k + 1]);
+    }
+  }
+  // behind the barrier: every read of B's and C's rows by this workgroup has returned
+  __device__ __forceinline__ void arrive(const SsmLaunch& a, uint32_t r) {
+    // (the zero the compiler cannot see through keeps the address a per-lane value: with an
+    // address it knows to be the same in every lane it would combine the lanes' additions and
+    // hand the result out again at once, waiting for it here)
+    uint32_t zero = 0;
+    asm volatile("" : "+v"(zero) :: "memory");
+    if (threadIdx.x == 0)
+      ticket = __hip_atomic_fetch_add(a.conv_arrivals + size_t(r) * kArrivalStride + zero, 1u, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // at the end of the kernel: the last workgroup of the request to have read B's and C's rows
+  // moves them on, sixteen bytes of channels per lane of the first wavefront
+  __device__ __forceinline__ void close(const SsmLaunch& a, uint32_t r) {
+    if ((threadIdx.x >> 6) != 0) return;
+    // the ticket is looked at here and no earlier: the wavefront must not wait for it above
+    asm volatile("" : "+v"(ticket) :: "memory");
+    const uint32_t drawn = __builtin_amdgcn_readfirstlane(ticket);
+    if (drawn != gridDim.x - 1 || threadIdx.x * V >= kShared) return;
+    const size_t row_bytes = size_t(conv_dim) * sizeof(E);
+    // thread 0's channel is the first of [B | C]
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(reinterpret_cast<uintptr_t>(win)));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(reinterpret_cast<uintptr_t>(win) >> 32));
+    uint8_t* rows = reinterpret_cast<uint8_t*>((uint64_t(hi) << 32) | lo) + size_t(threadIdx.x) * 16;
+    const uint8_t* token = static_cast<const uint8_t*>(a.conv_u) +
+                           (size_t(r) * conv_dim + (conv_dim - kShared)) * sizeof(E) + size_t(threadIdx.x) * 16;
+    Vec<E> next[K - 1];
+#pragma unroll
+    for (int k = 0; k < K - 2; ++k) next[k] = load_vec<E>(rows + (k + 1) * row_bytes);
+    next[K - 2] = load_vec<E>(token);
+#pragma unroll
+    for (int k = 0; k < K - 1; ++k) store_vec<E>(rows + k * row_bytes, next[k]);
+    if (threadIdx.x == 0)
+      __hip_atomic_store(a.conv_arrivals + size_t(r) * kArrivalStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+};
+
 // The same update at the Mamba-2 head shape, headdim 64 x dstate 128, with everything the shape
 // fixes folded in at compile time: a row's 128 values in 32 adjacent lanes, THREADS / 32 rows per
 // pass, one pass.  What the general kernel computes at run time (row geometry, loop bounds) sits
@@ -165,7 +288,8 @@ __global__ __launch_bounds__(THREADS) void ssm_update_kernel(SsmLaunch a) {
 // The step is 2574 us at batch 64 with the first shape, 2581 us with the second.
 constexpr uint64_t kShortLaunchTiles = 80 * 128;        // fp32 state: below this many (head, request) tiles, 512 threads
 constexpr uint64_t kSmallLaunchTiles16 = 96 * 128;      // bf16 state (measured crossover between 64 and 128 requests)
-template <typename E, int THREADS, bool ARITHMETIC_FIRST>
+// CONVK: taps of the layer's convolution done here (FusedConv), 0: x, B and C are read as given.
+template <typename E, int THREADS, bool ARITHMETIC_FIRST, int CONVK = 0>
 __global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a) {
   constexpr uint32_t N = 128, Pd = 64, kLanesPerRow = 32, kRowsPerPass = THREADS / kLanesPerRow;
   constexpr int kRows = Pd / kRowsPerPass;
@@ -176,8 +300,14 @@ __global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a)
   const uint32_t handle = a.handles[r];
   const float dt = a.dt[size_t(r) * H + h];
   const float Ah = a.A[h];
-  const float4 Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
-  const float4 Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
+  float4 Bv, Cv;
+  [[maybe_unused]] FusedConv<E, CONVK ? CONVK : 2, 64> conv;
+  if constexpr (CONVK == 0) {
+    Bv = load4<E>(static_cast<const E*>(a.B) + size_t(r) * N + 4 * col);
+    Cv = load4<E>(static_cast<const E*>(a.C) + size_t(r) * N + 4 * col);
+  } else {
+    conv.request_token(a, r, h);
+  }
   const uint64_t off = translate_offset(a.P, handle, 1);
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
   if (off == ~0ull) {
@@ -185,11 +315,12 @@ __global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a)
     if (tid < Pd) yrow[tid] = 0.f;
     return;
   }
+  if constexpr (CONVK != 0) conv.request_window(a.P.arena + off, uint64_t(H) * Pd * N * 4);
   float* tile = reinterpret_cast<float*>(a.P.arena + off) + size_t(h) * Pd * N;
   const __amdgpu_buffer_rsrc_t rsrc = tile_descriptor(tile, Pd * N * 4);
   const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
   float decay = 0.f;
-  if (ARITHMETIC_FIRST) {
+  if (ARITHMETIC_FIRST && CONVK == 0) {
     // nothing below may move above this point: B, C and the decay are in registers before the
     // first state load goes out
     decay = expf(dt * Ah);
@@ -202,9 +333,19 @@ __global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a)
   for (int k = 0; k < kRows; ++k) {
     const uint32_t p = row0 + k * kRowsPerPass;
     s[k] = as_float4(load_tile(rsrc, (p * N + 4 * col) * 4));
-    xs[k] = load_elem<E>(xrow + p);
+    if constexpr (CONVK == 0) xs[k] = load_elem<E>(xrow + p);
   }
-  if (!ARITHMETIC_FIRST) decay = expf(dt * Ah);
+  if constexpr (CONVK != 0) {
+    __shared__ __align__(16) float staged[decltype(conv)::kStaged];
+    conv.finish(staged);
+    __syncthreads();
+    conv.arrive(a, r);
+    Bv = *reinterpret_cast<const float4*>(staged + 4 * col);
+    Cv = *reinterpret_cast<const float4*>(staged + N + 4 * col);
+#pragma unroll
+    for (int k = 0; k < kRows; ++k) xs[k] = staged[2 * N + row0 + k * kRowsPerPass];
+  }
+  if (!ARITHMETIC_FIRST || CONVK != 0) decay = expf(dt * Ah);
 #pragma unroll
   for (int k = 0; k < kRows; ++k) {
     const uint32_t p = row0 + k * kRowsPerPass;
@@ -218,6 +359,7 @@ __global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a)
     const float part = sum_half32_into_upper_row(v.x * Cv.x + v.y * Cv.y + v.z * Cv.z + v.w * Cv.w);
     if (col == kLanesPerRow - 1) yrow[p] = part;
   }
+  if constexpr (CONVK != 0) conv.close(a, r);
 }
 
 // ---------------------------------------------------------------------------
@@ -259,12 +401,17 @@ __device__ __forceinline__ uint32_t bf16_round_bits(float f) {   // round to nea
 // heads in 1024 threads, 1595 us for two heads in 512 threads with four rows per lane, 1598 us
 // for 256 threads; at batch 128 / 256: 3036 / 5920 against 3010 / 5742 us).
 // PS: compile-time headdim (0 = read it from the launch), as NS for dstate.
-template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0>
+// CONVK: taps of the layer's convolution done here (FusedConv; headdim 64 x dstate 128 only), 0: x, B
+// and C are read as given.
+template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0, int CONVK = 0>
 __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch a) {
+  static_assert(CONVK == 0 || (NS == 128 && PS == 64 && EXACT), "the convolution is fused at the Mamba-2 head shape only");
   constexpr uint32_t TPH = THREADS / HPB;            // threads per head
   const uint32_t h = blockIdx.x * HPB + threadIdx.x / TPH, r = blockIdx.y, tid = threadIdx.x % TPH;
   const uint32_t H = a.heads, Pd = PS ? uint32_t(PS) : a.headdim;
   const uint32_t N = NS ? uint32_t(NS) : a.dstate;
+  [[maybe_unused]] FusedConv<E, CONVK ? CONVK : 2, 64 * HPB> conv;
+  if constexpr (CONVK != 0) conv.request_token(a, r, blockIdx.x * HPB);
   const uint64_t off = translate_offset(a.P, a.handles[r], 1);
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
   if (off == ~0ull) {
@@ -279,11 +426,16 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
   const float dt = a.dt[size_t(r) * H + h];
   const float decay = expf(dt * a.A[h]);
   float Bv[8], Cv[8];
-  load8<E>(static_cast<const E*>(a.B) + size_t(r) * N + 8 * col, Bv);
-  load8<E>(static_cast<const E*>(a.C) + size_t(r) * N + 8 * col, Cv);
+  if constexpr (CONVK == 0) {
+    load8<E>(static_cast<const E*>(a.B) + size_t(r) * N + 8 * col, Bv);
+    load8<E>(static_cast<const E*>(a.C) + size_t(r) * N + 8 * col, Cv);
+  } else {
+    conv.request_window(a.P.arena + off, uint64_t(H) * Pd * N * 2);
+  }
   const E* xrow = static_cast<const E*>(a.x) + (size_t(r) * H + h) * Pd;
   uint16_t* tile = reinterpret_cast<uint16_t*>(a.P.arena + off) + size_t(h) * Pd * N;
   const __amdgpu_buffer_rsrc_t rsrc = tile_descriptor(tile, Pd * N * 2);
+  [[maybe_unused]] const float* staged_x = nullptr;
 
   for (uint32_t pbase = row0; pbase < Pd; pbase += rpi * ROWS) {
     u32x4s raw[ROWS];
@@ -293,8 +445,21 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
       const uint32_t p = pbase + k * rpi;
       if (EXACT || p < Pd) {
         raw[k] = load_tile(rsrc, (p * N + 8 * col) * 2);
-        xs[k] = load_elem<E>(xrow + p);
+        if constexpr (CONVK == 0) xs[k] = load_elem<E>(xrow + p);
       }
+    }
+    if constexpr (CONVK != 0) {
+      if (pbase == row0) {      // the first pass's state is on its way: now the convolution
+        __shared__ __align__(16) float staged[decltype(conv)::kStaged];
+        conv.finish(staged);
+        __syncthreads();
+        conv.arrive(a, r);
+        load8<float>(staged + 8 * col, Bv);
+        load8<float>(staged + 128 + 8 * col, Cv);
+        staged_x = staged + 256 + (threadIdx.x / TPH) * 64;
+      }
+#pragma unroll
+      for (int k = 0; k < ROWS; ++k) xs[k] = staged_x[pbase + k * rpi];
     }
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
@@ -324,12 +489,49 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
       if ((EXACT || p < Pd) && col == 0) yrow[p] = part;
     }
   }
+  if constexpr (CONVK != 0) conv.close(a, r);
+}
+
+}  // namespace
+
+bool ssm_may_fuse_conv(uint32_t taps_k, uint32_t heads, uint32_t headdim, uint32_t dstate) {
+  return taps_k == 4 && heads != 0 && headdim == 64 && dstate == 128;
+}
+
+bool ssm_fuses_conv(uint32_t taps_k, uint32_t heads, uint32_t headdim, uint32_t dstate,
+                    uint32_t state_dtype, uint32_t batch) {
+  return ssm_may_fuse_conv(taps_k, heads, headdim, dstate) &&
+         (state_dtype == 1 || uint64_t(heads) * batch < kShortLaunchTiles);
+}
+
+namespace {
+
+// the kernels that run the layer's four-tap convolution themselves (headdim 64 x dstate 128)
+template <typename E>
+hipError_t launch_with_conv(const SsmLaunch& a, hipStream_t s) {
+  const dim3 grid(a.heads, a.batch);
+  if (a.state_dtype == 1) {
+    const bool small16 = uint64_t(a.heads) * a.batch < kSmallLaunchTiles16;
+    if (small16 || a.heads % 2 != 0)
+      ssm_update_bf16state_kernel<E, 512, 2, 128, true, 1, 64, 4><<<grid, dim3(512), 0, s>>>(a);
+    else
+      ssm_update_bf16state_kernel<E, 1024, 2, 128, true, 2, 64, 4><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+  } else {
+    ssm_update_mamba2_kernel<E, 512, false, 4><<<grid, dim3(512), 0, s>>>(a);
+  }
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   if (a.batch == 0) return hipSuccess;
+  if (a.conv_k != 0) {
+    if (!ssm_fuses_conv(a.conv_k, a.heads, a.headdim, a.dstate, a.state_dtype, a.batch) || !a.conv_u || !a.conv_taps ||
+        !a.conv_bias || !a.conv_arrivals)
+      return hipErrorInvalidValue;
+    return a.dtype == 0 ? launch_with_conv<float>(a, s) : launch_with_conv<uint16_t>(a, s);
+  }
   const dim3 grid(a.heads, a.batch);
   // a head's tile is headdim x dstate/4 16-byte accesses: big tiles get 1024 threads
   const bool big = uint64_t(a.headdim) * (a.dstate / 4) >= 1024;

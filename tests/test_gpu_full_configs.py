@@ -131,6 +131,42 @@ def test_jamba_batch64_variants_of_the_ssm_block(state_dtype, conv_kernel):
     ses.close()
 
 
+@pytest.mark.parametrize("state_dtype", ["f32", "bf16"])
+def test_long_launch_with_the_convolution_inside_the_recurrence_kernel(state_dtype):
+    """112 requests at the Jamba head shapes (1 attention + 7 SSM layers) with a 4-tap window:
+    launches long enough for the 1024-thread recurrence kernels.  With a bf16 state (two heads
+    per workgroup) the kernel runs the convolution itself; with an fp32 state a launch this long
+    takes the convolution as a launch of its own.  Four steps, so that the window's rows for B
+    and C, which every workgroup of a request reads and the last of them moves on, turn over
+    completely; sampled requests, windows compared byte for byte after every step."""
+    base = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    spec = inputs.with_conv(inputs.with_state_dtype(base, state_dtype) if state_dtype != "f32" else base, 4)
+    sc = inputs.make_scenario(spec, "uniform_short", 112, seed=1006)
+    ses = _session(sc, fill_byte=0xFF)
+    rng = np.random.default_rng(6)
+    sample = _sample(sc, 5, rng, always=[0, sc.batch - 1])
+    ses.fill(threads=16, requests=sample)
+    conv = inputs.conv_weights(spec, sc.seed)
+    refs = {r: RequestReference(spec, sc.seed, r, int(sc.ctx[r])) for r in sample}
+    a, n = spec.ssm_state_bytes, spec.conv_window_bytes
+    ulp = 2.0 ** -7
+    for step in range(4):
+        inp = inputs.step_inputs(spec, sc.batch, sc.seed, step=step)
+        if state_dtype == "bf16" and step > 0:       # each step judged from the state the GPU stored
+            for r, ref in refs.items():
+                for ls in range(spec.n_ssm):
+                    ref.load_block(ls, ses.read_unit(int(ses.ssm[ls, r])))
+        o, y = ses.step(inp, conv=conv)
+        _check_sample(ses, refs, inp, o, y, "conv inside, %s state, step %d" % (state_dtype, step), conv=conv,
+                      tol_state=TOL if state_dtype == "f32" else ulp)
+        for r, ref in refs.items():
+            for ls in range(spec.n_ssm):
+                assert np.array_equal(ses.read_unit(int(ses.ssm[ls, r]))[a: a + n],
+                                      ref.pools.unit_view(int(ref.ssm[ls, 0]))[a: a + n]), \
+                    "window of layer %d request %d after step %d" % (ls, r, step)
+    ses.close()
+
+
 def test_mixed_long_batch32_with_migration_there_and_back():
     """Config 3: long-context mix, KV pool at 95 % occupancy; 1024 pages of
     capacity move to the SSM pool between two steps and come back before a third."""

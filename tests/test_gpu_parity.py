@@ -742,8 +742,11 @@ def test_remap_migration_at_jamba_unit_sizes_and_argument_checks():
 
 @pytest.mark.parametrize("dtype,state_dtype,K,H,P,N", [
     ("f32", "f32", 4, 4, 32, 16),        # generic fp32 kernels
-    ("bf16", "f32", 4, 8, 64, 128),      # the Mamba-2 head shape (specialised recurrence kernel)
-    ("bf16", "bf16", 3, 8, 64, 128),     # bf16 state blocks, three taps
+    ("bf16", "f32", 4, 8, 64, 128),      # the Mamba-2 head shape: the recurrence kernel runs the convolution itself
+    ("bf16", "bf16", 4, 8, 64, 128),     # the same with bf16 state blocks
+    ("f32", "f32", 4, 3, 64, 128),       # the same with fp32 inputs (four channels per lane), odd head count
+    ("f32", "bf16", 4, 2, 64, 128),
+    ("bf16", "bf16", 3, 8, 64, 128),     # bf16 state blocks, three taps: convolution as a launch of its own
     ("bf16", "f32", 2, 3, 8, 8),         # two taps, odd head count
 ])
 def test_short_convolution_in_front_of_the_recurrence(dtype, state_dtype, K, H, P, N):
@@ -763,7 +766,10 @@ def test_short_convolution_in_front_of_the_recurrence(dtype, state_dtype, K, H, 
         ref_o, ref_y = op.decode_step(spec.layer_kinds, kv, sc.ctx, inp["q"], ssm, None, inp["dt"],
                                       inp["A"], None, None, xbc=inp["xbc"], conv_w=w, conv_b=b)
         o, y = g.step(inp, conv=(w, b))
-        _check_outputs(spec, o, y, ref_o, ref_y, "conv step %d" % step)
+        # from its second step on a bf16 state differs between the sides by an ulp of its storage
+        # type where the exact value sits on a rounding tie, and y with it
+        _check_outputs(spec, o, y, ref_o, ref_y, "conv step %d" % step,
+                       y_tol=2.0 ** -7 if state_dtype == "bf16" and step > 0 else None)
         for ls in range(spec.n_ssm):
             got = g.conv_windows(ls)
             for r in range(sc.batch):
