@@ -97,7 +97,10 @@ typedef struct avmp_config {
                                       also keeps, behind the state, the inputs of the last K-1 tokens
                                       as [K-1][H*P + 2*N] elements (oldest first), and a step takes
                                       xbc / conv_taps / conv_bias instead of x, B, C.  Needs H*P and
-                                      N to be multiples of 16/element_bytes */
+                                      N to be multiples of 16/element_bytes.  With K = 4, P = 64 and
+                                      N = 128 the recurrence kernel runs the convolution itself and
+                                      the pools hold 8 MiB more device memory (one arrival counter
+                                      per request of the largest batch, a cache line apart) */
   uint32_t ssm_pad_to_kv_page;     /* 0 (default): the block has its native size.  1: the sizing of a
                                       unified pool (Background, "Existing Cache Management"; the
                                       padded_unified baseline of Evaluation, "Experimental Setup"):
