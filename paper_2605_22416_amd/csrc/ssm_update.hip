@@ -387,9 +387,13 @@ __device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float (&v)[8]
   }
 }
 
-__device__ __forceinline__ uint32_t bf16_round_bits(float f) {   // round to nearest, ties to even
-  const uint32_t u = __float_as_uint(f);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// Two fp32 values rounded to bf16 (to nearest, ties to even) and packed, `lo` in the low half:
+// the conversion instruction of this chip, one operation for what takes nine on the integer side.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // HPB heads share one workgroup (THREADS / HPB threads each), so that a workgroup
@@ -474,7 +478,7 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
           const float lo = decay * __uint_as_float(w[j] << 16) + dtx * Bv[2 * j];
           const float hi = decay * __uint_as_float(w[j] & 0xFFFF0000u) + dtx * Bv[2 * j + 1];
           part += lo * Cv[2 * j] + hi * Cv[2 * j + 1];
-          out[j] = bf16_round_bits(lo) | (bf16_round_bits(hi) << 16);
+          out[j] = pack_bf16_pair(lo, hi);
         }
         const u32x4s packed = {out[0], out[1], out[2], out[3]};
         store_tile(rsrc, (p * N + 8 * col) * 2, packed);
