@@ -15,9 +15,11 @@ namespace {
 // the head's [P][N] fp32 tile (32 KiB at 64 x 128) is streamed once in and once
 // out with 16-byte accesses; a row's N values sit in N/4 adjacent lanes, which
 // also reduce y = sum_n S*C.  The state is touched exactly once per step, so
-// its loads and stores are non-temporal (policy below).  1024-thread workgroups
-// move a whole tile in one burst of loads followed by one burst of stores;
-// on MI355X that measured 6.3 TB/s against 5.2 TB/s for 256-thread groups.
+// its loads and stores are non-temporal (policy below).  A workgroup moves a whole
+// tile in one burst of loads followed by one burst of stores: workgroups of 256
+// threads that walk their tile in four passes measured 5.2 TB/s on MI355X, one-burst
+// workgroups of 512 or 1024 threads 6.3 - 6.7 TB/s (which of the two: see the kernel
+// for the Mamba-2 head shape below).
 // ---------------------------------------------------------------------------
 // The state tile goes through buffer accesses so that its cache policy can be
 // named: non-temporal (touched once per step) and sc1 scope on top of it.  Against
