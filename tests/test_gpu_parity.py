@@ -364,23 +364,29 @@ def test_churn_between_steps_keeps_device_table_in_sync(backing):
     g.close()
 
 
-def test_decode_step_replayed_from_a_hip_graph_matches_eager_steps():
+@pytest.mark.parametrize("conv_kernel", [0, 4])
+def test_decode_step_replayed_from_a_hip_graph_matches_eager_steps(conv_kernel):
     """A decode step captured in a HIP graph (no allocation, no memset nodes, no
     host work in the captured region) and replayed several times, with eager
     work and synchronisations in between, gives bit-identical outputs to eager
-    steps on a twin session."""
+    steps on a twin session.  With a convolution window the recurrence kernel
+    runs the convolution and its arrival counters must be back at zero after
+    every replay."""
     import torch
     from paper_2605_22416_amd import binding as av
     gh = _harness()
     spec = inputs.scaled_down(inputs.JAMBA_MINI, 1)
+    if conv_kernel:
+        spec = inputs.with_conv(spec, conv_kernel)
     ctx = [17, 300, 1100, 64]
     sc = inputs.make_scenario(spec, "uniform_short", len(ctx), seed=12, ctx=ctx)
     inp = inputs.step_inputs(spec, len(ctx), seed=12)
+    conv = inputs.conv_weights(spec, seed=12) if conv_kernel else None
     eager, graphed = gh.GpuPools(sc), gh.GpuPools(sc)
     eager.fill()
     graphed.fill()
-    st_e, keep_e, o_e, y_e = eager.prepare_step(inp)
-    st_g, keep_g, o_g, y_g = graphed.prepare_step(inp)
+    st_e, keep_e, o_e, y_e = eager.prepare_step(inp, conv=conv)
+    st_g, keep_g, o_g, y_g = graphed.prepare_step(inp, conv=conv)
     # first step eagerly on both: sizes the work buffer, leaves nothing queued
     eager.launch(st_e)
     graphed.launch(st_g)
@@ -403,6 +409,9 @@ def test_decode_step_replayed_from_a_hip_graph_matches_eager_steps():
         scratch = torch.randn(1 << 20, device=gh.DEV)
         assert torch.isfinite(scratch.sum()).item()
     assert np.array_equal(eager.states(0), graphed.states(0))
+    if conv_kernel:
+        for ls in range(spec.n_ssm):
+            assert np.array_equal(eager.conv_windows(ls), graphed.conv_windows(ls))
     assert av.avmp_device_faults(graphed.p) == (av.AVMP_OK, 0)
     eager.close()
     graphed.close()

@@ -19,7 +19,7 @@ from tests.test_gpu_parity import _both, _check_outputs, _check_states, _check_t
 pytestmark = pytest.mark.gpu
 
 
-def _draw(seed):
+def _draw(seed, conv_inside=False):
     rng = np.random.default_rng([seed, 777])
     dtype = "bf16" if rng.random() < 0.6 else "f32"
     vec = 8 if dtype == "bf16" else 4
@@ -32,6 +32,8 @@ def _draw(seed):
     H = int(rng.integers(1, 7))
     P = int(rng.choice([1, 3, 8, 24, 32, 64, 128]))
     K = int(rng.choice([0, 0, 2, 3, 4]))
+    if conv_inside:      # the shape at which the recurrence kernel runs the convolution itself
+        H, P, N, K = int(rng.integers(1, 10)), 64, 128, 4
     kinds = tuple(int(k) for k in rng.integers(0, 2, size=int(rng.integers(2, 5))))
     if inputs.ATTN not in kinds:
         kinds = kinds + (inputs.ATTN,)
@@ -48,8 +50,18 @@ def _draw(seed):
 
 @pytest.mark.parametrize("seed", range(120))
 def test_random_shape(seed):
+    _run(seed, *_draw(seed), steps=2)
+
+
+@pytest.mark.parametrize("seed", range(500, 524))
+def test_random_shape_with_the_convolution_inside_the_recurrence_kernel(seed):
+    """Headdim 64 x dstate 128 with four taps, everything else drawn; four steps, so that the
+    window turns over completely."""
+    _run(seed, *_draw(seed, conv_inside=True), steps=4)
+
+
+def _run(seed, spec, ctx, rng, refused, steps):
     from paper_2605_22416_amd import binding as av
-    spec, ctx, rng, refused = _draw(seed)
     what = "seed %d: %s ctx %s" % (seed, spec, ctx)
     print(what, flush=True)
     sc = inputs.make_scenario(spec, "tiny", len(ctx), seed=1000 + seed, ctx=ctx, headroom=1.6)
@@ -68,7 +80,7 @@ def test_random_shape(seed):
     op, g, kv, ssm = _both(sc, poison=True)
     conv = inputs.conv_weights(spec, seed=seed) if spec.conv_kernel else None
     extra = dict(xbc=None, conv_w=None, conv_b=None)
-    for step in range(2):
+    for step in range(steps):
         if step == 1:                      # capacity moves between the steps, live units with it
             donor = int(rng.integers(0, 2))
             n = max(1, int(av.avmp_stats(g.p)["free"][donor]) // 2)
