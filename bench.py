@@ -166,7 +166,7 @@ def _worker_init():
 
 def host_workers():
     """Worker processes for the all-cores leg: the cores this process may run on, at most 16
-    (a GPU machine's share per GPU)."""
+    (a host's share of cores per GPU on an eight-GPU node)."""
     try:
         n = len(os.sched_getaffinity(0))
     except (AttributeError, OSError):
