@@ -45,6 +45,30 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) {
   return __uint_as_float(b << 16);
 }
 
+// Sums and maxima over the lanes of a row of 16 without going through LDS: data-parallel-primitive
+// moves (quad permutes, then mirrors of 8 and of 16 lanes: after each step every lane holds the
+// result of a group twice as large).
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_moved(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+// every lane of a 16-lane row ends up with the row's sum
+__device__ __forceinline__ float sum_row16(float v) {
+  v += dpp_moved<0xB1>(v);      // quad_perm [1,0,3,2]
+  v += dpp_moved<0x4E>(v);      // quad_perm [2,3,0,1]
+  v += dpp_moved<0x141>(v);     // row_half_mirror
+  v += dpp_moved<0x140>(v);     // row_mirror
+  return v;
+}
+// every lane of a 16-lane row ends up with the row's maximum
+__device__ __forceinline__ float max_row16(float v) {
+  v = fmaxf(v, dpp_moved<0xB1>(v));
+  v = fmaxf(v, dpp_moved<0x4E>(v));
+  v = fmaxf(v, dpp_moved<0x141>(v));
+  v = fmaxf(v, dpp_moved<0x140>(v));
+  return v;
+}
+
 template <typename E>
 __device__ __forceinline__ float load_elem(const E* p);
 template <>

@@ -217,9 +217,14 @@ __global__ __launch_bounds__(64 * kGenericHeadsPerBlock) void attn_generic_kerne
   float m = -INFINITY, l = 0.f;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
 
+  // the next page's handle is translated while this page is worked on
+  auto offset_of = [&](uint32_t page) -> uint64_t {
+    return translate_offset(a.P, a.handles[size_t(r) * a.max_pages + page], 0);
+  };
+  uint64_t off_next = offset_of(p0);
   for (uint32_t page = p0; page < p1; ++page) {
-    const uint32_t h = a.handles[size_t(r) * a.max_pages + page];
-    const uint64_t off = translate_offset(a.P, h, 0);
+    const uint64_t off = off_next;
+    if (page + 1 < p1) off_next = offset_of(page + 1);
     if (off == ~0ull) {                         // wave-uniform: skip the page, count it
       if (lane == 0) count_fault(a.P);
       continue;
@@ -244,19 +249,17 @@ __global__ __launch_bounds__(64 * kGenericHeadsPerBlock) void attn_generic_kerne
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
     s = (t < n_valid) ? s * scale_log2 : -INFINITY;                 // tail slots never count
-    float pm = s;
-    for (int o = 8; o; o >>= 1) pm = fmaxf(pm, __shfl_xor(pm, o));
-    const float m_new = fmaxf(m, pm);
+    // the 16 token lanes of a row of the wavefront: maxima and sums by moves inside the row
+    const float m_new = fmaxf(m, max_row16(s));
     const float alpha = exp2f(m - m_new);
     const float p = exp2f(s - m_new);
-    float ps = p;
-    for (int o = 8; o; o >>= 1) ps += __shfl_xor(ps, o);
-    l = l * alpha + ps;
+    l = l * alpha + sum_row16(p);
     m = m_new;
     const E* vbase = pg + size_t(G) * 16 * D + size_t(g) * D * 16;  // [D][16]
     float pt[16];
 #pragma unroll
-    for (int tt = 0; tt < 16; ++tt) pt[tt] = __shfl(p, tt);
+    for (int tt = 0; tt < 16; ++tt)         // every row of the wavefront holds the same 16 weights
+      pt[tt] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p), tt));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t d = lane + 64 * i;

@@ -47,21 +47,6 @@ __device__ __forceinline__ u32x4s as_words(float4 v) {
   return w;
 }
 
-// Sums over the lanes of a row without going through LDS: data-parallel-primitive moves inside
-// a row of 16 lanes (quad permutes, then mirrors of 8 and of 16 lanes: after each step every lane
-// holds the sum of a group twice as large), and lane 15 of a row added into the row behind it.
-template <int CTRL, int ROW_MASK = 0xF>
-__device__ __forceinline__ float dpp_moved(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
-}
-// every lane of a 16-lane row ends up with the row's sum
-__device__ __forceinline__ float sum_row16(float v) {
-  v += dpp_moved<0xB1>(v);      // quad_perm [1,0,3,2]
-  v += dpp_moved<0x4E>(v);      // quad_perm [2,3,0,1]
-  v += dpp_moved<0x141>(v);     // row_half_mirror
-  v += dpp_moved<0x140>(v);     // row_mirror
-  return v;
-}
 // lanes 16..31 and 48..63 end up with the sum of their 32-lane half of the wavefront
 __device__ __forceinline__ float sum_half32_into_upper_row(float v) {
   v = sum_row16(v);
