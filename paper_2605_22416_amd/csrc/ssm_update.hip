@@ -274,7 +274,9 @@ struct FusedConv {
 //     batch 64 on).  With 512 threads this order is the slowest of all (87.0 at batch 64).
 // The step is 2574 us at batch 64 with the first shape, 2581 us with the second.
 constexpr uint64_t kShortLaunchTiles = 80 * 128;        // fp32 state: below this many (head, request) tiles, 512 threads
-constexpr uint64_t kSmallLaunchTiles16 = 96 * 128;      // bf16 state (measured crossover between 64 and 128 requests)
+constexpr uint64_t kSmallLaunchTiles16 = 128 * 128;     // bf16 state: below, 512 threads and state first;
+constexpr uint64_t kLongLaunchTiles16 = 224 * 128;      // from here on two heads per 1024 threads, arithmetic first
+constexpr uint64_t kConvLongLaunchTiles16 = 160 * 128;  // with the convolution inside: two heads per 1024 threads from here on
 // CONVK: taps of the layer's convolution done here (FusedConv), 0: x, B and C are read as given.
 template <typename E, int THREADS, bool ARITHMETIC_FIRST, int CONVK = 0>
 __global__ __launch_bounds__(THREADS) void ssm_update_mamba2_kernel(SsmLaunch a) {
@@ -383,27 +385,43 @@ __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// HPB heads share one workgroup (THREADS / HPB threads each), so that a workgroup
-// still moves a 32 KiB burst (two heads of 1024 threads together: 51.5 us per layer at
-// batch 64, against 55.7 us with one head and 54.4 us with four, all with the row geometry
-// worked out at run time).  With headdim and dstate compile-time constants a head per
-// workgroup of 512 threads is the fastest shape at headdim 64 x dstate 128 for launches of up
-// to about 96 requests (the step with a bf16 state at batch 64: 1560 us against 1569 us for two
-// heads in 1024 threads, 1595 us for two heads in 512 threads with four rows per lane, 1598 us
-// for 256 threads; at batch 128 / 256: 3036 / 5920 against 3010 / 5742 us).
+__device__ __forceinline__ uint64_t same_in_every_lane(uint64_t v) {
+  const uint32_t lo = uint32_t(__builtin_amdgcn_readfirstlane(int(uint32_t(v))));
+  const uint32_t hi = uint32_t(__builtin_amdgcn_readfirstlane(int(uint32_t(v >> 32))));
+  return (uint64_t(hi) << 32) | lo;
+}
+
+// HPB heads share one workgroup (THREADS / HPB threads each), so that a workgroup of 1024
+// threads still moves a 32 KiB burst.  At headdim 64 x dstate 128 three forms are used, by the
+// length of the launch (us per layer on the decode step at 64 / 96 / 128 / 192 / 256 requests
+// of 128 heads):
+//   * a head per workgroup of 512 threads, state asked for first   48.8 / 70.8 / 93.3 / 142.4 / 189.3
+//   * the same with B, C and the decay in registers before that    49.5 / 71.2 / 93.2 / 139.5 / 182.0
+//   * two heads per workgroup of 1024 threads, arithmetic first    50.8 / 72.9 / 95.2 / 141.4 / 179.8
+//   (two heads in 1024 threads, state first                        50.3 / 72.2 / 93.7 / 140.3 / 186.4)
+// as with the fp32 state: short launches are mostly ramp-up and drain and want their loads out
+// at once; long ones want a row stored the moment it arrives.
 // PS: compile-time headdim (0 = read it from the launch), as NS for dstate.
 // CONVK: taps of the layer's convolution done here (FusedConv; headdim 64 x dstate 128 only), 0: x, B
 // and C are read as given.
-template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0, int CONVK = 0>
+template <typename E, int THREADS, int ROWS, int NS, bool EXACT, int HPB = 1, int PS = 0, int CONVK = 0,
+          bool ARITHMETIC_FIRST = false>
 __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch a) {
   static_assert(CONVK == 0 || (NS == 128 && PS == 64 && EXACT), "the convolution is fused at the Mamba-2 head shape only");
   constexpr uint32_t TPH = THREADS / HPB;            // threads per head
-  const uint32_t h = blockIdx.x * HPB + threadIdx.x / TPH, r = blockIdx.y, tid = threadIdx.x % TPH;
+  // which of the workgroup's heads: the same for a whole wavefront, and said so, or the tile's
+  // buffer descriptor counts as a per-lane value and every access to it is wrapped in a loop
+  // over the distinct descriptors of the wavefront
+  const uint32_t head_in_wg = HPB == 1 ? 0u : uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x / TPH)));
+  const uint32_t h = blockIdx.x * HPB + head_in_wg, r = blockIdx.y, tid = threadIdx.x % TPH;
   const uint32_t H = a.heads, Pd = PS ? uint32_t(PS) : a.headdim;
   const uint32_t N = NS ? uint32_t(NS) : a.dstate;
   [[maybe_unused]] FusedConv<E, CONVK ? CONVK : 2, 64 * HPB> conv;
   if constexpr (CONVK != 0) conv.request_token(a, r, blockIdx.x * HPB);
-  const uint64_t off = translate_offset(a.P, a.handles[r], 1);
+  // (the block's offset is the same in every lane; behind the per-thread branches of the
+  // convolution the compiler no longer sees that, and the descriptor built on it would be
+  // taken for a per-lane value)
+  const uint64_t off = same_in_every_lane(translate_offset(a.P, a.handles[r], 1));
   float* yrow = a.y + (size_t(r) * H + h) * Pd;
   if (off == ~0ull) {
     if (tid == 0) count_fault(a.P);
@@ -420,6 +438,13 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
   if constexpr (CONVK == 0) {
     load8<E>(static_cast<const E*>(a.B) + size_t(r) * N + 8 * col, Bv);
     load8<E>(static_cast<const E*>(a.C) + size_t(r) * N + 8 * col, Cv);
+    if constexpr (ARITHMETIC_FIRST) {
+      // nothing below may move above this point: B, C and the decay are in registers before the
+      // first state load goes out
+      asm volatile("" :: "v"(decay), "v"(Bv[0]), "v"(Bv[1]), "v"(Bv[2]), "v"(Bv[3]), "v"(Bv[4]), "v"(Bv[5]),
+                   "v"(Bv[6]), "v"(Bv[7]), "v"(Cv[0]), "v"(Cv[1]), "v"(Cv[2]), "v"(Cv[3]), "v"(Cv[4]),
+                   "v"(Cv[5]), "v"(Cv[6]), "v"(Cv[7]) : "memory");
+    }
   } else {
     conv.request_window(a.P.arena + off, uint64_t(H) * Pd * N * 2);
   }
@@ -447,7 +472,7 @@ __global__ __launch_bounds__(THREADS) void ssm_update_bf16state_kernel(SsmLaunch
         conv.arrive(a, r);
         load8<float>(staged + 8 * col, Bv);
         load8<float>(staged + 128 + 8 * col, Cv);
-        staged_x = staged + 256 + (threadIdx.x / TPH) * 64;
+        staged_x = staged + 256 + head_in_wg * 64;
       }
 #pragma unroll
       for (int k = 0; k < ROWS; ++k) xs[k] = staged_x[pbase + k * rpi];
@@ -502,8 +527,7 @@ template <typename E>
 hipError_t launch_with_conv(const SsmLaunch& a, hipStream_t s) {
   const dim3 grid(a.heads, a.batch);
   if (a.state_dtype == 1) {
-    const bool small16 = uint64_t(a.heads) * a.batch < kSmallLaunchTiles16;
-    if (small16 || a.heads % 2 != 0)
+    if (uint64_t(a.heads) * a.batch < kConvLongLaunchTiles16 || a.heads % 2 != 0)
       ssm_update_bf16state_kernel<E, 512, 2, 128, true, 1, 64, 4><<<grid, dim3(512), 0, s>>>(a);
     else
       ssm_update_bf16state_kernel<E, 1024, 2, 128, true, 2, 64, 4><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
@@ -532,11 +556,14 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
   if (a.state_dtype == 1) {
     const bool big16 = uint64_t(a.headdim) * (a.dstate / 8) >= 1024;
     const bool small16 = uint64_t(a.heads) * a.batch < kSmallLaunchTiles16;
+    const bool long16 = uint64_t(a.heads) * a.batch >= kLongLaunchTiles16;
     if (a.dtype == 0) {
-      if (exact128 && a.headdim == 64 && small16)     // the Mamba-2 shape: a head per workgroup of 512 threads
+      if (exact128 && a.headdim == 64 && small16)     // the Mamba-2 shape
         ssm_update_bf16state_kernel<float, 512, 2, 128, true, 1, 64><<<grid, dim3(512), 0, s>>>(a);
-      else if (exact128 && a.headdim == 64 && a.heads % 2 == 0)
-        ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      else if (exact128 && a.headdim == 64 && (!long16 || a.heads % 2 != 0))
+        ssm_update_bf16state_kernel<float, 512, 2, 128, true, 1, 64, 0, true><<<grid, dim3(512), 0, s>>>(a);
+      else if (exact128 && a.headdim == 64)
+        ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2, 64, 0, true><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<float, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<float, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);
@@ -545,8 +572,10 @@ hipError_t launch_ssm(const SsmLaunch& a, hipStream_t s) {
     } else {
       if (exact128 && a.headdim == 64 && small16)
         ssm_update_bf16state_kernel<uint16_t, 512, 2, 128, true, 1, 64><<<grid, dim3(512), 0, s>>>(a);
-      else if (exact128 && a.headdim == 64 && a.heads % 2 == 0)
-        ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2, 64><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
+      else if (exact128 && a.headdim == 64 && (!long16 || a.heads % 2 != 0))
+        ssm_update_bf16state_kernel<uint16_t, 512, 2, 128, true, 1, 64, 0, true><<<grid, dim3(512), 0, s>>>(a);
+      else if (exact128 && a.headdim == 64)
+        ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2, 64, 0, true><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128 && a.heads % 2 == 0)
         ssm_update_bf16state_kernel<uint16_t, 1024, 2, 128, true, 2><<<dim3(a.heads / 2, a.batch), dim3(1024), 0, s>>>(a);
       else if (exact128) ssm_update_bf16state_kernel<uint16_t, 1024, 1, 128, true><<<grid, dim3(1024), 0, s>>>(a);

@@ -131,22 +131,29 @@ def test_jamba_batch64_variants_of_the_ssm_block(state_dtype, conv_kernel):
     ses.close()
 
 
-@pytest.mark.parametrize("state_dtype", ["f32", "bf16"])
-def test_long_launch_with_the_convolution_inside_the_recurrence_kernel(state_dtype):
-    """112 requests at the Jamba head shapes (1 attention + 7 SSM layers) with a 4-tap window:
-    launches long enough for the 1024-thread recurrence kernels.  With a bf16 state (two heads
-    per workgroup) the kernel runs the convolution itself; with an fp32 state a launch this long
-    takes the convolution as a launch of its own.  Four steps, so that the window's rows for B
-    and C, which every workgroup of a request reads and the last of them moves on, turn over
-    completely; sampled requests, windows compared byte for byte after every step."""
+@pytest.mark.parametrize("state_dtype,batch,conv_kernel", [
+    ("f32", 112, 4),      # 1024-thread recurrence kernel, convolution as a launch of its own
+    ("bf16", 112, 4),     # a head per workgroup, convolution inside
+    ("bf16", 232, 4),     # two heads per workgroup of 1024 threads, convolution inside
+    ("bf16", 160, 0),     # a head per workgroup, arithmetic before the state loads
+    ("bf16", 232, 0),     # two heads per workgroup, arithmetic before the state loads
+])
+def test_long_launches_of_the_recurrence_kernels(state_dtype, batch, conv_kernel):
+    """Batches of 112 ... 232 requests at the Jamba head shapes (1 attention + 7 SSM layers):
+    launches long enough for the forms of the recurrence kernels that short launches do not
+    reach.  Four steps, so that a convolution window's rows for B and C, which every workgroup
+    of a request reads and the last of them moves on, turn over completely; sampled requests,
+    windows compared byte for byte after every step."""
     base = inputs.scaled_down(inputs.JAMBA_MINI, 1)
-    spec = inputs.with_conv(inputs.with_state_dtype(base, state_dtype) if state_dtype != "f32" else base, 4)
-    sc = inputs.make_scenario(spec, "uniform_short", 112, seed=1006)
+    spec = inputs.with_state_dtype(base, state_dtype) if state_dtype != "f32" else base
+    if conv_kernel:
+        spec = inputs.with_conv(spec, conv_kernel)
+    sc = inputs.make_scenario(spec, "uniform_short", batch, seed=1006)
     ses = _session(sc, fill_byte=0xFF)
     rng = np.random.default_rng(6)
     sample = _sample(sc, 5, rng, always=[0, sc.batch - 1])
     ses.fill(threads=16, requests=sample)
-    conv = inputs.conv_weights(spec, sc.seed)
+    conv = inputs.conv_weights(spec, sc.seed) if conv_kernel else None
     refs = {r: RequestReference(spec, sc.seed, r, int(sc.ctx[r])) for r in sample}
     a, n = spec.ssm_state_bytes, spec.conv_window_bytes
     ulp = 2.0 ** -7
@@ -157,10 +164,10 @@ def test_long_launch_with_the_convolution_inside_the_recurrence_kernel(state_dty
                 for ls in range(spec.n_ssm):
                     ref.load_block(ls, ses.read_unit(int(ses.ssm[ls, r])))
         o, y = ses.step(inp, conv=conv)
-        _check_sample(ses, refs, inp, o, y, "conv inside, %s state, step %d" % (state_dtype, step), conv=conv,
-                      tol_state=TOL if state_dtype == "f32" else ulp)
+        _check_sample(ses, refs, inp, o, y, "%s state, batch %d, conv %d, step %d" % (state_dtype, batch, conv_kernel, step),
+                      conv=conv, tol_state=TOL if state_dtype == "f32" else ulp)
         for r, ref in refs.items():
-            for ls in range(spec.n_ssm):
+            for ls in range(spec.n_ssm if conv_kernel else 0):
                 assert np.array_equal(ses.read_unit(int(ses.ssm[ls, r]))[a: a + n],
                                       ref.pools.unit_view(int(ref.ssm[ls, 0]))[a: a + n]), \
                     "window of layer %d request %d after step %d" % (ls, r, step)
