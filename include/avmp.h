@@ -366,7 +366,9 @@ enum {
   AVMP_K_SSM = 2,              /* SSM state update (per layer) */
   AVMP_K_MIGRATE_COPY = 3,     /* migration copy + remap */
   AVMP_K_TABLE = 4,            /* table scatter + zero fill of new SSM blocks */
-  AVMP_K_CONV = 5,             /* short convolution in front of the recurrence (per layer) */
+  AVMP_K_CONV = 5,             /* short convolution in front of the recurrence (per layer); no
+                                  launches where the recurrence kernel runs it itself: its time
+                                  is then part of AVMP_K_SSM */
   AVMP_K_ATTENTION_PREPARE = 6,/* run plan + translation of all KV handles (once per step) */
   AVMP_K_COUNT = 7
 };
