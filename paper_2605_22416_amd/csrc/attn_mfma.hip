@@ -125,8 +125,9 @@ struct PrepareArgs {
   uint4* desc;                // [runs] out
   float* o;                   // [n_attn][batch][n_q_heads * head_dim]: rows of empty requests
   uint32_t batch, max_pages, runs, append, n_attn, row_floats;
-  uint32_t pitch_log2, page_tiles;   // translation blocks: see attn_prepare_kernel
+  uint32_t pitch_log2, page_tiles, row_groups, n_tiles;   // translation blocks: see attn_prepare_kernel
 };
+constexpr uint32_t kPrepareBlocks = 2048;     // translating blocks of a launch, at most
 
 __device__ void plan_block(const PrepareArgs& a) {
   // per thread: (cost << 32 | pages) summed over its segment of the batch, inclusive
@@ -243,26 +244,40 @@ __global__ __launch_bounds__(1024) void attn_prepare_kernel(PrepareArgs a) {
     plan_block(a);
     return;
   }
-  // One entry per thread.  Rows of up to 1024 pages: a block takes 1024 >> pitch_log2 whole
-  // rows, each on a power-of-two pitch; longer rows: page_tiles blocks of 1024 entries per
-  // row.  Entries beyond the request's pages are left as they are.
-  const uint32_t tile = blockIdx.x - 1;
-  const uint32_t row_group = tile / a.page_tiles, page_tile = tile % a.page_tiles;
-  const uint32_t row = (row_group << (10 - a.pitch_log2)) + (threadIdx.x >> a.pitch_log2);
-  const uint32_t page = page_tile * 1024 + (threadIdx.x & ((1u << a.pitch_log2) - 1u));
-  if (row >= a.n_attn * a.batch || page >= a.max_pages) return;
-  const uint32_t r = row % a.batch;
-  const uint64_t e = uint64_t(row) * a.max_pages + page;
-  // the handle is requested together with the context length, not after it
-  const uint32_t n_ctx = attended_tokens(a.ctx, r, a.append);
-  uint32_t h = a.handles[e];
-  asm volatile("" : "+v"(h));
-  if (page >= pages_of(n_ctx, a.max_pages)) return;
-  const uint64_t off = translate_offset(a.P, h, 0);
-  uint32_t slot = kDevUnmapped;
-  if (off == ~0ull) count_fault(a.P);
-  else slot = uint32_t(off / a.P.unit[0]);
-  a.slots[e] = slot;
+  // One entry per thread and tile.  Rows of up to 1024 pages: a tile is 1024 >> pitch_log2 whole
+  // rows, each on a power-of-two pitch; longer rows: page_tiles tiles of 1024 entries per row.
+  // Entries beyond the request's pages are left as they are.  The grid holds at most
+  // kPrepareBlocks translating blocks, which walk the tiles between them: a batch of long rows
+  // has far more tiles than pages to translate (516 requests with room for 16384 pages each,
+  // four of them that long: 33 k tiles of which 2.3 k hold pages; one block per tile took 137 us,
+  // nearly all of it the launching of blocks with nothing to do).
+  for (uint32_t tile = blockIdx.x - 1; tile < a.n_tiles; tile += gridDim.x - 1) {
+    // tiles are numbered page tile by page tile, so that the tiles of the rows' first 1024 pages,
+    // which every row with pages has, are dealt out evenly over the blocks
+    const uint32_t row_group = tile % a.row_groups, page_tile = tile / a.row_groups;
+    if (a.page_tiles > 1) {
+      // long rows: the tile lies within one row (row_group); beyond that row's pages there is
+      // nothing to do, and no handle is asked for
+      if (row_group >= a.n_attn * a.batch) continue;
+      const uint32_t row_pages = pages_of(attended_tokens(a.ctx, row_group % a.batch, a.append), a.max_pages);
+      if (page_tile * 1024u >= row_pages) continue;
+    }
+    const uint32_t row = (row_group << (10 - a.pitch_log2)) + (threadIdx.x >> a.pitch_log2);
+    const uint32_t page = page_tile * 1024 + (threadIdx.x & ((1u << a.pitch_log2) - 1u));
+    if (row >= a.n_attn * a.batch || page >= a.max_pages) continue;
+    const uint32_t r = row % a.batch;
+    const uint64_t e = uint64_t(row) * a.max_pages + page;
+    // the handle is requested together with the context length, not after it
+    const uint32_t n_ctx = attended_tokens(a.ctx, r, a.append);
+    uint32_t h = a.handles[e];
+    asm volatile("" : "+v"(h));
+    if (page >= pages_of(n_ctx, a.max_pages)) continue;
+    const uint64_t off = translate_offset(a.P, h, 0);
+    uint32_t slot = kDevUnmapped;
+    if (off == ~0ull) count_fault(a.P);
+    else slot = uint32_t(off / a.P.unit[0]);
+    a.slots[e] = slot;
+  }
 }
 
 // Where run w of KV head g keeps a partial result: a run leaves at most two, slot 1 for
@@ -645,9 +660,13 @@ hipError_t launch_attention_prepare(const AttnLaunch& a, const uint32_t* handles
   p.page_tiles = a.max_pages > 1024 ? (a.max_pages + 1023) / 1024 : 1;
   const uint64_t rows = uint64_t(n_attn) * a.batch;
   const uint32_t rows_per_block = 1024u >> pitch_log2;
-  const uint64_t blocks = 1 + (rows + rows_per_block - 1) / rows_per_block * p.page_tiles;
-  if (rows > 0xFFFFFFFFull || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  attn_prepare_kernel<<<dim3(uint32_t(blocks)), dim3(1024), 0, s>>>(p);
+  const uint64_t row_groups = (rows + rows_per_block - 1) / rows_per_block;
+  const uint64_t tiles = row_groups * p.page_tiles;
+  if (rows > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  p.row_groups = uint32_t(row_groups);
+  p.n_tiles = uint32_t(tiles);
+  const uint32_t blocks = 1 + uint32_t(tiles < kPrepareBlocks ? tiles : kPrepareBlocks);
+  attn_prepare_kernel<<<dim3(blocks), dim3(1024), 0, s>>>(p);
   return hipGetLastError();
 }
 
